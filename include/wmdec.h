@@ -1,0 +1,209 @@
+/*
+ * wmdec -- fused latent -> frame convolutional decoder for AMD MI355X (gfx950).
+ *
+ * C ABI of libwmdec.so.  The library implements the memory-bound decoder stage
+ * that the paper's vertical operator fusion targets (Sec. IV-A, Eq. 8: the
+ * unfused graph materialises every Conv2d / GroupNorm / SiLU result in HBM;
+ * Sec. IV-B-1, Eq. 9: the fused graph reads its input once and writes its
+ * output once).  On gfx950 the fusion is: one GroupNorm statistics pass, then
+ * normalise + SiLU applied while an input tile is staged into LDS for an
+ * implicit-GEMM convolution on the matrix cores, nearest-2x upsampling folded
+ * into that gather, bias and residual added in the epilogue.
+ *
+ * Conventions (all entry points)
+ *  - Every tensor pointer is a DEVICE pointer owned by the caller; the library
+ *    never allocates, frees or copies device memory and never synchronises.
+ *    All work is enqueued on `stream` (a hipStream_t passed as void*, NULL =
+ *    the default stream).  Host-side handles (wmdec_decoder) are library-owned.
+ *  - Activations are dense NHWC ("channels last"): element (n, y, x, c) of a
+ *    logical [N,C,H,W] tensor lives at ((n*H + y)*W + x)*C + c.  Only
+ *    decoder_run's latent input and frame output are NCHW.
+ *  - Tensor pointers must be 16-byte aligned.
+ *  - Return value: 0 (WMDEC_OK) or a negative wmdec_status.  Argument errors
+ *    are detected before anything is launched; wmdec_last_error() returns a
+ *    thread-local description of the last failure.  No exception crosses the ABI.
+ *  - Same inputs give bitwise identical outputs (no order-dependent atomics).
+ */
+#ifndef WMDEC_H
+#define WMDEC_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  WMDEC_OK = 0,
+  WMDEC_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, bad enum */
+  WMDEC_ERR_UNSUPPORTED = -2, /* valid in principle, not implemented for this dtype / shape */
+  WMDEC_ERR_SHAPE = -3,       /* sizes inconsistent (c % groups != 0, ...) */
+  WMDEC_ERR_WORKSPACE = -4,   /* workspace missing or too small */
+  WMDEC_ERR_HIP = -5          /* a HIP call or kernel launch failed */
+} wmdec_status;
+
+/* Storage / arithmetic types.  F32: fp32 storage, fp32 FMA arithmetic.
+ * BF16 / F16: 16-bit storage, matrix-core (MFMA) products of that type with
+ * fp32 accumulation; statistics, normalisation, SiLU, softmax, bias and
+ * residual adds are always fp32. */
+typedef enum { WMDEC_F32 = 0, WMDEC_BF16 = 1, WMDEC_F16 = 2 } wmdec_dtype;
+
+const char* wmdec_last_error(void);
+const char* wmdec_status_string(int status);
+
+/* ------------------------------------------------------------------------
+ * GroupNorm statistics pass (operator list of Sec. IV-B-1; the paper does not
+ * say how per-group statistics survive spatial tiling -- here they are a
+ * separate streaming pass).
+ *   group g of sample n = channels [g*c/groups, (g+1)*c/groups) over all h*w
+ *   pixels;  mean[n*groups+g] = average,  rstd[...] = 1/sqrt(biased variance + eps).
+ * x: [n,h,w,c] NHWC of x_dtype.  mean, rstd: fp32 [n*groups] outputs.
+ * workspace: at least wmdec_gn_stats_workspace_bytes(...) bytes, contents
+ * undefined before and after.  Errors: c % groups != 0 -> WMDEC_ERR_SHAPE. */
+size_t wmdec_gn_stats_workspace_bytes(int n, int h, int w, int c, int groups);
+int wmdec_gn_stats(const void* x, int x_dtype, int n, int h, int w, int c, int groups, float eps,
+                   float* mean, float* rstd, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Weight packing.  Convolution kernels read weights in the packed order
+ * [ky][kx][cout][cin] (cin contiguous) in the operand type `op_dtype`
+ * (F32 for the fp32 path, else BF16 or F16).  src is the logical
+ * [cout][cin][k][k] tensor (k = 1 or 3) of src_dtype (F32 or BF16).
+ * BF16 -> F16 conversion is exact for normal-range values.  */
+size_t wmdec_conv_packed_bytes(int cout, int cin, int k, int op_dtype);
+int wmdec_pack_conv_weights(const void* src, int src_dtype, int cout, int cin, int k,
+                            void* packed, int op_dtype, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Fused GroupNorm-apply -> SiLU -> 3x3 convolution (+bias, +residual):
+ * Conv2d, GroupNorm, SiLU of Sec. IV-B-1 in one kernel (Eq. 9).
+ *   u[n,y,x,ci] = act(gamma[ci]*(x - mean[n,g])*rstd[n,g] + beta[ci]),  act = SiLU if apply_silu
+ *   y[n,oy,ox,co] = bias[co] + sum_{ky,kx,ci} W[co,ci,ky,kx] * u[n,oy+ky-1,ox+kx-1,ci] (+ residual)
+ * with u = 0 outside the image (padding acts on the activated tensor).
+ * mean == NULL (then rstd, gamma, beta are ignored) skips normalisation and
+ * activation: a plain convolution.  act_dtype: type of x, residual and of the
+ * MFMA operands (w_packed must be packed for it).  y_dtype: act_dtype or F32.
+ * bias (fp32 [cout]) and residual ([n,h,w,cout], act_dtype) may be NULL.
+ * x and y must not overlap.  gamma, beta: fp32 [cin]. */
+int wmdec_gn_silu_conv3x3(const void* x, int act_dtype, const float* mean, const float* rstd,
+                          const float* gamma, const float* beta, int groups, int apply_silu,
+                          const void* w_packed, const float* bias, const void* residual,
+                          void* y, int y_dtype, int n, int h, int w, int cin, int cout, void* stream);
+
+/* 1x1 convolution (a GEMM over pixels) with the same optional normalise-on-load,
+ * bias and residual; used for the attention projections and the channel-changing
+ * ResBlock shortcut.  w_packed: packed with k = 1. */
+int wmdec_gn_conv1x1(const void* x, int act_dtype, const float* mean, const float* rstd,
+                     const float* gamma, const float* beta, int groups, int apply_silu,
+                     const void* w_packed, const float* bias, const void* residual,
+                     void* y, int y_dtype, int n, int h, int w, int cin, int cout, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Upsample -> Conv2d fused (first two operators of the chain in Sec. IV-B-1):
+ *   y[n,oy,ox,co] = bias[co] + sum W[co,ci,ky,kx] * x[n,(oy+ky-1)>>1,(ox+kx-1)>>1,ci]
+ * for 0 <= oy+ky-1 < 2*h_in and 0 <= ox+kx-1 < 2*w_in, zero otherwise.
+ * x: [n,h_in,w_in,cin]; y: [n,2*h_in,2*w_in,cout].  The upsampled tensor is
+ * never materialised. */
+int wmdec_upsample2x_conv3x3(const void* x, int act_dtype, const void* w_packed, const float* bias,
+                             void* y, int y_dtype, int n, int h_in, int w_in, int cin, int cout,
+                             void* stream);
+
+/* Stand-alone nearest-neighbour 2x upsample, y[n,oy,ox,c] = x[n,oy>>1,ox>>1,c];
+ * bit-exact copy of elements of `dtype`. */
+int wmdec_upsample2x_nearest(const void* x, void* y, int dtype, int n, int h_in, int w_in, int c,
+                             void* stream);
+
+/* ------------------------------------------------------------------------
+ * Layout / type conversion between the logical NCHW order and the library's
+ * NHWC order: dst = convert(src) element by element (round to nearest even
+ * when narrowing). */
+int wmdec_nchw_to_nhwc(const void* src, int src_dtype, void* dst, int dst_dtype,
+                       int n, int c, int h, int w, void* stream);
+int wmdec_nhwc_to_nchw(const void* src, int src_dtype, void* dst, int dst_dtype,
+                       int n, int c, int h, int w, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Mid-block single-head self-attention with residual (flash-style, the score
+ * matrix is never materialised):
+ *   hn = gamma*(x-mean)*rstd+beta (no SiLU);  [q|k|v] = Wqkv hn + bqkv;
+ *   o = softmax_rows(q k^T / sqrt(c)) v;  y = x + Wo o + bo.
+ * Tokens are the h*w pixels of one sample.  x, y: [n,h,w,c] of act_dtype
+ * (BF16 or F16).  wqkv_packed: the [3c][c] matrix (rows q, then k, then v)
+ * packed as a 1x1 convolution with cout = 3c; wo_packed: [c][c] likewise.
+ * bqkv: fp32 [3c]; bo: fp32 [c].  c must be 512.  workspace: at least
+ * wmdec_attention_workspace_bytes(n,h,w,c) bytes. */
+size_t wmdec_attention_workspace_bytes(int n, int h, int w, int c);
+int wmdec_attention(const void* x, int act_dtype, const float* mean, const float* rstd,
+                    const float* gamma, const float* beta, int groups,
+                    const void* wqkv_packed, const float* bqkv, const void* wo_packed, const float* bo,
+                    void* y, int n, int h, int w, int c,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Whole decoder:  latent z[N,latent_c,h,w] -> frame [N,out_c,8h,8w]
+ * (the I_t <- VAE_Decode(z_t) step of Alg. 1 / Alg. 2).
+ * Graph: conv_in 3x3; mid = ResBlock, attention, ResBlock; per level
+ * `resblocks_per_level` ResBlocks (the first maps the previous level's channel
+ * count, with a 1x1-conv shortcut when it changes) followed -- except after the
+ * last level -- by upsample-conv; then GroupNorm -> SiLU -> conv_out.
+ * ResBlock(x) = S(x) + conv3x3(SiLU(GN(conv3x3(SiLU(GN(x)))))). */
+typedef struct wmdec_decoder wmdec_decoder; /* opaque, host memory, library-owned */
+
+typedef struct {
+  int latent_c, latent_h, latent_w; /* 4, 60, 90 */
+  int num_levels;                   /* 1..4 */
+  int level_channels[4];            /* 512, 512, 256, 128 */
+  int resblocks_per_level;          /* 3 */
+  int groups;                       /* 32 */
+  float eps;                        /* 1e-6 */
+  int out_c;                        /* 3 */
+  int act_dtype;                    /* WMDEC_BF16 or WMDEC_F16: storage of activations and MFMA operand type */
+  int max_batch;                    /* largest batch decoder_run will be given */
+} wmdec_decoder_config;
+
+/* Fills *cfg with the 720x480 decoder above (act_dtype = WMDEC_F16, max_batch = 4). */
+void decoder_default_config(wmdec_decoder_config* cfg);
+
+/* Validates cfg and builds the host-side plan.  Allocates no device memory. */
+int decoder_create(const wmdec_decoder_config* cfg, wmdec_decoder** out);
+int decoder_destroy(wmdec_decoder* dec);
+
+/* Canonical weight blob (what the caller provides to decoder_pack_weights):
+ * parameters in execution order, each at a 256-byte aligned offset; conv /
+ * linear weights are BF16 [cout][cin][k][k], biases, gamma, beta are F32.
+ * decoder_num_weights / decoder_weight_info enumerate them; names are
+ * "conv_in.w", "mid.res1.norm1.gamma", "mid.attn.q.w", "up.2.res0.shortcut.w",
+ * "up.0.upsample.b", "norm_out.beta", "conv_out.w", ...  */
+size_t decoder_weights_bytes(const wmdec_decoder* dec);
+int decoder_num_weights(const wmdec_decoder* dec);
+int decoder_weight_info(const wmdec_decoder* dec, int index, const char** name, size_t* offset,
+                        size_t* bytes, int* dtype, int shape[4]);
+int decoder_weight_offset(const wmdec_decoder* dec, const char* name, size_t* offset, size_t* bytes);
+
+/* Packed blob (what decoder_run reads): conv weights re-ordered / converted for
+ * the kernels, q/k/v fused into one matrix, small parameters copied.  `packed`
+ * must hold decoder_packed_bytes(dec) bytes.  Done once per set of weights. */
+size_t decoder_packed_bytes(const wmdec_decoder* dec);
+int decoder_pack_weights(const wmdec_decoder* dec, const void* weights, void* packed, void* stream);
+
+/* Scratch for activations and statistics of one decoder_run of `batch` frames. */
+size_t decoder_workspace_bytes(const wmdec_decoder* dec, int batch);
+int decoder_set_workspace(wmdec_decoder* dec, void* workspace, size_t bytes);
+
+/* latent: [batch,latent_c,h,w] NCHW, BF16.  packed: from decoder_pack_weights.
+ * out: [batch,out_c,8h,8w] NCHW, F32.  1 <= batch <= max_batch.  Enqueues the
+ * whole graph on `stream`; no host synchronisation.  Calls that share one
+ * decoder (hence one workspace) must be ordered on the same stream. */
+int decoder_run(wmdec_decoder* dec, const void* latent, const void* packed, void* out, int batch,
+                void* stream);
+
+/* Number of kernel launches one decoder_run enqueues, and the algorithmic
+ * FLOP count (2*k*k*cin*cout per output pixel of every convolution plus
+ * 4*T*T*c per attention) of one frame. */
+int decoder_num_launches(const wmdec_decoder* dec);
+double decoder_flops_per_frame(const wmdec_decoder* dec);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WMDEC_H */

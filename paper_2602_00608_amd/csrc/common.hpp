@@ -1,0 +1,121 @@
+// Shared declarations of the wmdec HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/wmdec.h"
+
+namespace wmdec {
+
+// ---------------------------------------------------------------- 16-bit types
+// Storage types are raw bit patterns; conversions are explicit so that every
+// rounding point is visible in the kernels.
+struct bf16_t { uint16_t bits; };
+struct f16_t  { uint16_t bits; };
+
+__device__ __forceinline__ float to_float(float v) { return v; }
+__device__ __forceinline__ float to_float(bf16_t v) { return __uint_as_float(((uint32_t)v.bits) << 16); }
+__device__ __forceinline__ float to_float(f16_t v) {
+  _Float16 h; __builtin_memcpy(&h, &v.bits, 2); return (float)h;
+}
+
+template <typename T> __device__ __forceinline__ T from_float(float v);
+template <> __device__ __forceinline__ float from_float<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_float<bf16_t>(float v) {
+  // round to nearest even; NaN stays NaN
+  uint32_t u = __float_as_uint(v);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return bf16_t{(uint16_t)((u >> 16) | 0x40u)};
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return bf16_t{(uint16_t)(u >> 16)};
+}
+template <> __device__ __forceinline__ f16_t from_float<f16_t>(float v) {
+  _Float16 h = (_Float16)v;  // v_cvt_f16_f32: round to nearest even
+  f16_t r; __builtin_memcpy(&r.bits, &h, 2); return r;
+}
+
+// round a float through the 16-bit type T (identity for float)
+template <typename T> __device__ __forceinline__ float round_through(float v) { return to_float(from_float<T>(v)); }
+
+__device__ __forceinline__ float silu_f(float t) {
+  // t * sigmoid(t); exp2 of -t*log2(e) keeps it to one transcendental plus one reciprocal
+  return t * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * t));
+}
+
+// ---------------------------------------------------------------- host side
+void set_error(const char* fmt, ...);
+int hip_fail(hipError_t e, const char* what);
+
+#define WMDEC_REQUIRE(cond, code, ...)        \
+  do {                                        \
+    if (!(cond)) {                            \
+      ::wmdec::set_error(__VA_ARGS__);        \
+      return (code);                          \
+    }                                         \
+  } while (0)
+
+#define WMDEC_HIP(expr)                                           \
+  do {                                                            \
+    hipError_t e__ = (expr);                                      \
+    if (e__ != hipSuccess) return ::wmdec::hip_fail(e__, #expr);  \
+  } while (0)
+
+inline bool is_16bit(int dt) { return dt == WMDEC_BF16 || dt == WMDEC_F16; }
+inline bool valid_dtype(int dt) { return dt == WMDEC_F32 || is_16bit(dt); }
+inline size_t dtype_size(int dt) { return dt == WMDEC_F32 ? 4 : 2; }
+
+// Arguments of every convolution launch (3x3 / 1x1, optional fused pieces).
+struct ConvArgs {
+  const void* x = nullptr;       // input activations
+  int x_dtype = WMDEC_F32;       // storage type of x
+  int x_nchw = 0;                // 1: x is [n,cin,h_in,w_in] (decoder latent), else NHWC
+  const float* mean = nullptr;   // [n*groups] or null: no normalisation
+  const float* rstd = nullptr;
+  const float* gamma = nullptr;  // [cin]
+  const float* beta = nullptr;
+  int groups = 1;
+  int silu = 0;
+  const void* wt = nullptr;      // packed [k*k][cout][cin] in op dtype
+  int op_dtype = WMDEC_F32;      // arithmetic: F32 (FMA) or BF16 / F16 (operands rounded to it)
+  const float* bias = nullptr;   // [cout] or null
+  const void* res = nullptr;     // [n,h,w,cout] of res_dtype or null
+  int res_dtype = WMDEC_F32;
+  void* y = nullptr;
+  int y_dtype = WMDEC_F32;
+  int y_nchw = 0;                // 1: y is [n,cout,h,w] (decoder frame)
+  int n = 0, h = 0, w = 0;       // OUTPUT height / width
+  int cin = 0, cout = 0;
+  int ksize = 3;                 // 1 or 3
+  int upsample = 0;              // 1: input is [n,h/2,w/2,cin], gathered at (y>>1, x>>1)
+};
+
+// kernels_conv_direct.hip: general VALU convolution (any shape, all dtypes).
+int launch_conv_direct(const ConvArgs& a, hipStream_t s);
+// kernels_conv_mfma.hip: implicit-GEMM MFMA convolution; returns 1 if the shape
+// is not one it handles (caller falls back to the direct kernel), 0 if launched.
+bool conv_mfma_supported(const ConvArgs& a);
+int launch_conv_mfma(const ConvArgs& a, hipStream_t s);
+// picks the kernel
+int launch_conv(const ConvArgs& a, hipStream_t s);
+
+// kernels_gn.hip
+size_t gn_stats_workspace_bytes(int n, int h, int w, int c, int groups);
+int launch_gn_stats(const void* x, int x_dtype, int n, int h, int w, int c, int groups, float eps,
+                    float* mean, float* rstd, void* ws, size_t ws_bytes, hipStream_t s);
+
+// kernels_misc.hip
+int launch_upsample2x(const void* x, void* y, int dtype, int n, int h_in, int w_in, int c, hipStream_t s);
+int launch_pack_conv(const void* src, int src_dtype, int cout, int cin, int k, void* dst, int op_dtype,
+                     int dst_row_offset, int dst_rows_total, hipStream_t s);
+// dst[n][i][j] (dst_dtype) = src[n][j][i] (src_dtype); src is [rows=j][cols=i] with row stride src_ld
+int launch_transpose(const void* src, int src_dtype, void* dst, int dst_dtype, int batch, int rows, int cols,
+                     size_t src_ld, size_t src_batch_stride, size_t dst_ld, size_t dst_batch_stride, hipStream_t s);
+int launch_copy_f32(const float* src, float* dst, size_t count, hipStream_t s);
+
+// kernels_attn.hip
+// q,k: [n][t][ld] rows of d elements (16-bit type), vt: [n][d][t_pad] keys contiguous, o: [n][t][d]
+int launch_flash_attention(const void* q, const void* k, size_t qk_ld, size_t qk_batch_stride,
+                           const void* vt, int t_pad, void* o, int dtype, int n, int t, int d,
+                           float scale, hipStream_t s);
+
+}  // namespace wmdec

@@ -1,0 +1,170 @@
+// General convolution on the vector ALUs: any channel counts, any supported
+// dtype, 3x3 or 1x1, optional normalise(+SiLU)-on-load, folded nearest-2x
+// upsample, bias and residual in the epilogue, NHWC or NCHW at either end.
+// It is the fp32 path (operands and FMAs in fp32) and the path for shapes the
+// matrix-core kernel does not take (C_in = 4 of conv_in, C_out = 3 of conv_out).
+// For 16-bit operand types the activated input is rounded to that type before
+// the product and accumulated in fp32, i.e. the arithmetic of the MFMA kernel.
+#include "common.hpp"
+
+namespace wmdec {
+namespace {
+
+constexpr int TH = 8, TW = 8;     // output pixels per workgroup: 8 x 8
+constexpr int TCO = 64;           // output channels per workgroup
+constexpr int KC = 8;             // input channels per LDS stage
+constexpr int HALO = TW + 2;      // staged tile is (TH+2) x (TW+2) for 3x3
+
+__device__ __forceinline__ float load_as_float(const void* p, int dtype, size_t i) {
+  switch (dtype) {
+    case WMDEC_F32: return ((const float*)p)[i];
+    case WMDEC_BF16: return to_float(((const bf16_t*)p)[i]);
+    default: return to_float(((const f16_t*)p)[i]);
+  }
+}
+__device__ __forceinline__ void store_from_float(void* p, int dtype, size_t i, float v) {
+  switch (dtype) {
+    case WMDEC_F32: ((float*)p)[i] = v; break;
+    case WMDEC_BF16: ((bf16_t*)p)[i] = from_float<bf16_t>(v); break;
+    default: ((f16_t*)p)[i] = from_float<f16_t>(v); break;
+  }
+}
+__device__ __forceinline__ float round_op(float v, int op_dtype) {
+  switch (op_dtype) {
+    case WMDEC_F32: return v;
+    case WMDEC_BF16: return round_through<bf16_t>(v);
+    default: return round_through<f16_t>(v);
+  }
+}
+
+struct DirectParams {
+  const void* x; const float* mean; const float* rstd; const float* gamma; const float* beta;
+  const void* w; const float* bias; const void* res; void* y;
+  int x_dtype, op_dtype, res_dtype, y_dtype;
+  int x_nchw, y_nchw, silu, groups;
+  int n, h, w_out, cin, cout, ksize, upsample;
+  int tiles_x;
+};
+
+__global__ __launch_bounds__(256) void conv_direct_kernel(DirectParams p) {
+  __shared__ float s_in[(TH + 2) * HALO][KC + 1];
+  __shared__ float s_w[9][KC][TCO];
+  __shared__ float s_scale[KC], s_shift[KC];
+
+  const int tid = threadIdx.x;
+  const int tile = blockIdx.x;
+  const int ty0 = (tile / p.tiles_x) * TH, tx0 = (tile % p.tiles_x) * TW;
+  const int co0 = blockIdx.y * TCO;
+  const int n = blockIdx.z;
+  const int pad = p.ksize / 2;
+  const int taps = p.ksize * p.ksize;
+  const int h_in = p.upsample ? p.h / 2 : p.h, w_in = p.upsample ? p.w_out / 2 : p.w_out;
+  const int cpg = p.mean ? p.cin / p.groups : 1;
+
+  // thread -> 4 pixels (one row segment) x 4 output channels
+  const int pg = tid & 15, cg = tid >> 4;
+  const int py = pg >> 1, px0 = (pg & 1) * 4;
+  float acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+
+  const int halo_w = TW + 2 * pad, halo_h = TH + 2 * pad;
+  for (int c0 = 0; c0 < p.cin; c0 += KC) {
+    __syncthreads();
+    if (tid < KC) {
+      const int c = c0 + tid;
+      float sc = 1.f, sh = 0.f;
+      if (p.mean && c < p.cin) {
+        const int g = c / cpg;
+        sc = p.gamma[c] * p.rstd[n * p.groups + g];
+        sh = p.beta[c] - p.mean[n * p.groups + g] * sc;
+      }
+      s_scale[tid] = sc; s_shift[tid] = sh;
+    }
+    // weights of this channel chunk: s_w[tap][k][co]
+    for (int i = tid; i < taps * KC * TCO; i += 256) {
+      const int k = i % KC, co = (i / KC) % TCO, tap = i / (KC * TCO);
+      float v = 0.f;
+      if (co0 + co < p.cout && c0 + k < p.cin)
+        v = load_as_float(p.w, p.op_dtype, ((size_t)tap * p.cout + co0 + co) * p.cin + c0 + k);
+      s_w[tap][k][co] = v;
+    }
+    __syncthreads();
+    // activated input tile with halo; zero outside the (upsampled) image
+    for (int i = tid; i < halo_h * halo_w * KC; i += 256) {
+      const int k = i % KC, hp = i / KC;
+      const int hy = hp / halo_w, hx = hp % halo_w;
+      const int gy = ty0 + hy - pad, gx = tx0 + hx - pad;  // position on the output grid
+      const int c = c0 + k;
+      float v = 0.f;
+      if (gy >= 0 && gy < p.h && gx >= 0 && gx < p.w_out && c < p.cin) {
+        const int sy = p.upsample ? (gy >> 1) : gy, sx = p.upsample ? (gx >> 1) : gx;
+        const size_t idx = p.x_nchw ? (((size_t)n * p.cin + c) * h_in + sy) * w_in + sx
+                                    : (((size_t)n * h_in + sy) * w_in + sx) * p.cin + c;
+        v = load_as_float(p.x, p.x_dtype, idx);
+        if (p.mean) {
+          v = fmaf(v, s_scale[k], s_shift[k]);
+          if (p.silu) v = silu_f(v);
+        }
+        v = round_op(v, p.op_dtype);
+      }
+      s_in[hy * HALO + hx][k] = v;
+    }
+    __syncthreads();
+    for (int tap = 0; tap < taps; ++tap) {
+      const int ky = tap / p.ksize, kx = tap % p.ksize;
+#pragma unroll
+      for (int k = 0; k < KC; ++k) {
+        float a[4], b[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a[i] = s_in[(py + ky) * HALO + px0 + i + kx][k];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) b[j] = s_w[tap][k][cg * 4 + j];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+      }
+    }
+  }
+
+  const int oy = ty0 + py;
+  if (oy >= p.h) return;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int ox = tx0 + px0 + i;
+    if (ox >= p.w_out) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int co = co0 + cg * 4 + j;
+      if (co >= p.cout) continue;
+      float v = acc[i][j];
+      if (p.bias) v += p.bias[co];
+      const size_t nhwc = (((size_t)n * p.h + oy) * p.w_out + ox) * p.cout + co;
+      if (p.res) v += load_as_float(p.res, p.res_dtype, nhwc);
+      const size_t oi = p.y_nchw ? (((size_t)n * p.cout + co) * p.h + oy) * p.w_out + ox : nhwc;
+      store_from_float(p.y, p.y_dtype, oi, v);
+    }
+  }
+}
+
+}  // namespace
+
+int launch_conv_direct(const ConvArgs& a, hipStream_t s) {
+  DirectParams p;
+  p.x = a.x; p.mean = a.mean; p.rstd = a.rstd; p.gamma = a.gamma; p.beta = a.beta;
+  p.w = a.wt; p.bias = a.bias; p.res = a.res; p.y = a.y;
+  p.x_dtype = a.x_dtype; p.op_dtype = a.op_dtype; p.res_dtype = a.res_dtype; p.y_dtype = a.y_dtype;
+  p.x_nchw = a.x_nchw; p.y_nchw = a.y_nchw; p.silu = a.silu; p.groups = a.groups;
+  p.n = a.n; p.h = a.h; p.w_out = a.w; p.cin = a.cin; p.cout = a.cout; p.ksize = a.ksize; p.upsample = a.upsample;
+  p.tiles_x = (a.w + TW - 1) / TW;
+  const int tiles_y = (a.h + TH - 1) / TH;
+  dim3 grid((unsigned)(p.tiles_x * tiles_y), (unsigned)((a.cout + TCO - 1) / TCO), (unsigned)a.n);
+  hipLaunchKernelGGL(conv_direct_kernel, grid, dim3(256), 0, s, p);
+  WMDEC_HIP(hipGetLastError());
+  return WMDEC_OK;
+}
+
+}  // namespace wmdec

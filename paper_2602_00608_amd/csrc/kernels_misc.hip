@@ -1,0 +1,152 @@
+// Small data-movement kernels: nearest-2x upsample, weight packing, strided
+// transpose with type conversion (NCHW <-> NHWC, V -> V^T), fp32 copy.
+#include "common.hpp"
+
+namespace wmdec {
+namespace {
+
+struct alignas(16) Chunk16 { uint32_t w[4]; };
+
+// y[n,oy,ox,:] = x[n,oy>>1,ox>>1,:]; one 16-byte chunk per thread (c*esize % 16 == 0)
+__global__ __launch_bounds__(256) void upsample2x_vec(const Chunk16* __restrict__ x, Chunk16* __restrict__ y,
+                                                      int h_in, int w_in, int cpp /*chunks per pixel*/, size_t total) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int cc = (int)(i % cpp);
+  size_t pix = i / cpp;
+  const int ox = (int)(pix % (2 * w_in)); pix /= (2 * w_in);
+  const int oy = (int)(pix % (2 * h_in));
+  const size_t n = pix / (2 * h_in);
+  y[i] = x[((n * h_in + (oy >> 1)) * w_in + (ox >> 1)) * cpp + cc];
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void upsample2x_elem(const T* __restrict__ x, T* __restrict__ y,
+                                                       int h_in, int w_in, int c, size_t total) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int cc = (int)(i % c);
+  size_t pix = i / c;
+  const int ox = (int)(pix % (2 * w_in)); pix /= (2 * w_in);
+  const int oy = (int)(pix % (2 * h_in));
+  const size_t n = pix / (2 * h_in);
+  y[i] = x[((n * h_in + (oy >> 1)) * w_in + (ox >> 1)) * c + cc];
+}
+
+// dst[tap][row_off + co][ci] = convert(src[co][ci][tap])
+template <typename S, typename D>
+__global__ __launch_bounds__(256) void pack_conv_kernel(const S* __restrict__ src, D* __restrict__ dst, int cout, int cin,
+                                                        int taps, int row_off, int rows_total) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t total = (size_t)taps * cout * cin;
+  if (i >= total) return;
+  const int ci = (int)(i % cin);
+  const int co = (int)((i / cin) % cout);
+  const int tap = (int)(i / ((size_t)cin * cout));
+  dst[((size_t)tap * rows_total + row_off + co) * cin + ci] = from_float<D>(to_float(src[((size_t)co * cin + ci) * taps + tap]));
+}
+
+// dst[b][i][j] = src[b][j][i], 32x32 tiles through LDS
+template <typename S, typename D>
+__global__ __launch_bounds__(256) void transpose_kernel(const S* __restrict__ src, D* __restrict__ dst, int rows, int cols,
+                                                        size_t src_ld, size_t src_bs, size_t dst_ld, size_t dst_bs) {
+  __shared__ float tile[32][33];
+  const int b = blockIdx.z;
+  const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  for (int k = ty; k < 32; k += 8) {
+    const int r = r0 + k, c = c0 + tx;
+    if (r < rows && c < cols) tile[k][tx] = to_float(src[(size_t)b * src_bs + (size_t)r * src_ld + c]);
+  }
+  __syncthreads();
+  for (int k = ty; k < 32; k += 8) {
+    const int c = c0 + k, r = r0 + tx;
+    if (r < rows && c < cols) dst[(size_t)b * dst_bs + (size_t)c * dst_ld + r] = from_float<D>(tile[tx][k]);
+  }
+}
+
+__global__ __launch_bounds__(256) void copy_f32_kernel(const float* __restrict__ src, float* __restrict__ dst, size_t count) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < count) dst[i] = src[i];
+}
+
+template <typename S, typename D>
+int pack_t(const void* src, void* dst, int cout, int cin, int k, int row_off, int rows_total, hipStream_t s) {
+  const size_t total = (size_t)k * k * cout * cin;
+  hipLaunchKernelGGL((pack_conv_kernel<S, D>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                     (const S*)src, (D*)dst, cout, cin, k * k, row_off, rows_total);
+  WMDEC_HIP(hipGetLastError());
+  return WMDEC_OK;
+}
+
+template <typename S, typename D>
+int transpose_t(const void* src, void* dst, int batch, int rows, int cols, size_t sld, size_t sbs, size_t dld, size_t dbs, hipStream_t s) {
+  dim3 grid((unsigned)((cols + 31) / 32), (unsigned)((rows + 31) / 32), (unsigned)batch);
+  hipLaunchKernelGGL((transpose_kernel<S, D>), grid, dim3(256), 0, s, (const S*)src, (D*)dst, rows, cols, sld, sbs, dld, dbs);
+  WMDEC_HIP(hipGetLastError());
+  return WMDEC_OK;
+}
+
+template <typename S>
+int transpose_s(const void* src, void* dst, int dd, int batch, int rows, int cols, size_t sld, size_t sbs, size_t dld, size_t dbs, hipStream_t s) {
+  switch (dd) {
+    case WMDEC_F32: return transpose_t<S, float>(src, dst, batch, rows, cols, sld, sbs, dld, dbs, s);
+    case WMDEC_BF16: return transpose_t<S, bf16_t>(src, dst, batch, rows, cols, sld, sbs, dld, dbs, s);
+    default: return transpose_t<S, f16_t>(src, dst, batch, rows, cols, sld, sbs, dld, dbs, s);
+  }
+}
+
+}  // namespace
+
+int launch_upsample2x(const void* x, void* y, int dtype, int n, int h_in, int w_in, int c, hipStream_t s) {
+  const size_t es = dtype_size(dtype);
+  const size_t out_elems = (size_t)n * 4 * h_in * w_in * c;
+  if (((size_t)c * es) % 16 == 0) {
+    const int cpp = (int)((size_t)c * es / 16);
+    const size_t total = out_elems * es / 16;
+    hipLaunchKernelGGL(upsample2x_vec, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                       (const Chunk16*)x, (Chunk16*)y, h_in, w_in, cpp, total);
+  } else if (es == 4) {
+    hipLaunchKernelGGL(upsample2x_elem<uint32_t>, dim3((unsigned)((out_elems + 255) / 256)), dim3(256), 0, s,
+                       (const uint32_t*)x, (uint32_t*)y, h_in, w_in, c, out_elems);
+  } else {
+    hipLaunchKernelGGL(upsample2x_elem<uint16_t>, dim3((unsigned)((out_elems + 255) / 256)), dim3(256), 0, s,
+                       (const uint16_t*)x, (uint16_t*)y, h_in, w_in, c, out_elems);
+  }
+  WMDEC_HIP(hipGetLastError());
+  return WMDEC_OK;
+}
+
+int launch_pack_conv(const void* src, int src_dtype, int cout, int cin, int k, void* dst, int op_dtype,
+                     int dst_row_offset, int dst_rows_total, hipStream_t s) {
+  if (src_dtype == WMDEC_F32) {
+    switch (op_dtype) {
+      case WMDEC_F32: return pack_t<float, float>(src, dst, cout, cin, k, dst_row_offset, dst_rows_total, s);
+      case WMDEC_BF16: return pack_t<float, bf16_t>(src, dst, cout, cin, k, dst_row_offset, dst_rows_total, s);
+      default: return pack_t<float, f16_t>(src, dst, cout, cin, k, dst_row_offset, dst_rows_total, s);
+    }
+  }
+  switch (op_dtype) {
+    case WMDEC_F32: return pack_t<bf16_t, float>(src, dst, cout, cin, k, dst_row_offset, dst_rows_total, s);
+    case WMDEC_BF16: return pack_t<bf16_t, bf16_t>(src, dst, cout, cin, k, dst_row_offset, dst_rows_total, s);
+    default: return pack_t<bf16_t, f16_t>(src, dst, cout, cin, k, dst_row_offset, dst_rows_total, s);
+  }
+}
+
+int launch_transpose(const void* src, int src_dtype, void* dst, int dst_dtype, int batch, int rows, int cols,
+                     size_t src_ld, size_t src_batch_stride, size_t dst_ld, size_t dst_batch_stride, hipStream_t s) {
+  switch (src_dtype) {
+    case WMDEC_F32: return transpose_s<float>(src, dst, dst_dtype, batch, rows, cols, src_ld, src_batch_stride, dst_ld, dst_batch_stride, s);
+    case WMDEC_BF16: return transpose_s<bf16_t>(src, dst, dst_dtype, batch, rows, cols, src_ld, src_batch_stride, dst_ld, dst_batch_stride, s);
+    default: return transpose_s<f16_t>(src, dst, dst_dtype, batch, rows, cols, src_ld, src_batch_stride, dst_ld, dst_batch_stride, s);
+  }
+}
+
+int launch_copy_f32(const float* src, float* dst, size_t count, hipStream_t s) {
+  if (count == 0) return WMDEC_OK;
+  hipLaunchKernelGGL(copy_f32_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, src, dst, count);
+  WMDEC_HIP(hipGetLastError());
+  return WMDEC_OK;
+}
+
+}  // namespace wmdec

@@ -1,0 +1,134 @@
+"""The C-ABI library loads, exports every symbol the header declares, and its
+host-side logic (argument checks, decoder plan, weight table) behaves -- no GPU needed."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2602_00608_amd import synth, wmdec
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "wmdec.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return set(re.findall(r"\b((?:wmdec|decoder)_[a-z0-9_]+)\s*\(", text))
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    syms = header_symbols()
+    assert {"decoder_create", "decoder_run", "wmdec_gn_stats", "wmdec_gn_silu_conv3x3",
+            "wmdec_upsample2x_conv3x3", "wmdec_attention"} <= syms
+    l = wmdec.lib()
+    for s in syms:
+        assert hasattr(l, s), s
+    assert syms == set(wmdec.SIGNATURES), syms ^ set(wmdec.SIGNATURES)
+
+
+def test_no_torch_types_in_header():
+    text = open(os.path.join(ROOT, "include", "wmdec.h")).read()
+    assert "torch" not in text and "at::" not in text and "extern \"C\"" in text
+
+
+def test_default_config_and_weight_table_match_input_recipe():
+    dec = wmdec.Decoder()
+    cfg = dec.cfg
+    assert (cfg.latent_c, cfg.latent_h, cfg.latent_w) == (4, 60, 90)
+    assert list(cfg.level_channels) == [512, 512, 256, 128] and cfg.groups == 32 and cfg.out_c == 3
+    table = dec.weight_table()
+    spec = synth.decoder_weight_spec()
+    assert [t[0] for t in table] == [s[0] for s in spec]
+    for (name, off, nb, dt, shape), (_, sshape) in zip(table, spec):
+        full = tuple(sshape) + (1,) * (4 - len(sshape))
+        assert shape == full, name
+        assert dt == (wmdec.BF16 if name.endswith(".w") else wmdec.F32)
+        assert nb == int(np.prod(sshape)) * (2 if name.endswith(".w") else 4)
+        assert off % 256 == 0
+        assert dec.weight_offset(name) == (off, nb)
+    offs = [t[1] for t in table]
+    assert offs == sorted(offs) and dec.weights_bytes() >= offs[-1] + table[-1][2]
+    nparam = sum(int(np.prod(s[1])) for s in spec)
+    assert 49_000_000 < nparam < 50_000_000          # ~49.5 M parameters
+    # algorithmic work of one frame: 3329 GFLOP (convs) incl. 59.7 GFLOP attention core
+    assert abs(dec.flops_per_frame() / 1e9 - 3329) < 5
+    assert dec.workspace_bytes(1) > 3 * 480 * 720 * 256 * 2
+    assert dec.workspace_bytes(5) == 0                # beyond max_batch
+    dec.close()
+
+
+def test_flops_independent_count():
+    """Recount the decoder's FLOPs from the weight spec: every conv weight contributes
+    2*k*k*cin*cout per output pixel at the resolution its name implies."""
+    res = {"conv_in": 1, "mid": 1, "up.0": 1, "up.1": 2, "up.2": 4, "up.3": 8, "conv_out": 8}
+    total = 0.0
+    for name, shape in synth.decoder_weight_spec():
+        if not name.endswith(".w"):
+            continue
+        key = name[:-2].split(".res")[0].split(".attn")[0].split(".upsample")[0]
+        s = res[key] * (2 if ".upsample" in name else 1)
+        total += 2.0 * np.prod(shape) * (60 * s) * (90 * s)
+    total += 4.0 * 5400 * 5400 * 512
+    dec = wmdec.Decoder()
+    assert abs(dec.flops_per_frame() - total) / total < 1e-12
+    dec.close()
+
+
+def test_argument_errors_are_reported_without_a_gpu():
+    l = wmdec.lib()
+    assert l.wmdec_gn_stats(None, 0, 1, 1, 1, 32, 32, 1e-6, None, None, None, 0, None) == wmdec.ERR_INVALID_ARG
+    assert b"null" in l.wmdec_last_error()
+    # fake but aligned non-null addresses: the checks must fire before anything touches them
+    p = 0x1000
+    assert l.wmdec_gn_stats(p, 0, 1, 4, 4, 30, 32, 1e-6, p, p, p, 1 << 20, None) == wmdec.ERR_SHAPE
+    assert l.wmdec_gn_stats(p, 7, 1, 4, 4, 32, 32, 1e-6, p, p, p, 1 << 20, None) == wmdec.ERR_INVALID_ARG
+    assert l.wmdec_gn_stats(p, 0, 0, 4, 4, 32, 32, 1e-6, p, p, p, 1 << 20, None) == wmdec.ERR_INVALID_ARG
+    assert l.wmdec_gn_stats(p + 4, 0, 1, 4, 4, 32, 32, 1e-6, p, p, p, 1 << 20, None) == wmdec.ERR_INVALID_ARG
+    assert l.wmdec_gn_silu_conv3x3(p, 0, p, p, p, p, 32, 1, p, p, None, 2 * p, 0, 1, 4, 4, 48, 8, None) == wmdec.ERR_SHAPE
+    assert l.wmdec_gn_silu_conv3x3(p, 1, None, None, None, None, 32, 1, p, p, None, p, 1, 1, 4, 4, 32, 8, None) == wmdec.ERR_INVALID_ARG  # x == y
+    assert l.wmdec_gn_silu_conv3x3(p, 1, None, None, None, None, 32, 1, p, p, None, 2 * p, 2, 1, 4, 4, 32, 8, None) == wmdec.ERR_UNSUPPORTED
+    assert l.wmdec_attention(p, 1, p, p, p, p, 32, p, p, p, p, 2 * p, 1, 4, 4, 256, p, 1 << 30, None) == wmdec.ERR_UNSUPPORTED
+    assert l.wmdec_attention(p, 1, p, p, p, p, 32, p, p, p, p, 2 * p, 1, 4, 4, 512, p, 16, None) == wmdec.ERR_WORKSPACE
+    assert l.wmdec_upsample2x_nearest(p, p, 1, 1, 2, 2, 8, None) == wmdec.ERR_INVALID_ARG
+    assert l.wmdec_conv_packed_bytes(64, 64, 3, wmdec.F32) == 9 * 64 * 64 * 4
+    assert l.wmdec_conv_packed_bytes(64, 64, 2, wmdec.F32) == 0
+    assert l.wmdec_status_string(wmdec.ERR_WORKSPACE) == b"workspace missing or too small"
+    cfg = wmdec.decoder_default_config()
+    cfg.level_channels[2] = 250
+    h = ctypes.c_void_p()
+    assert l.decoder_create(ctypes.byref(cfg), ctypes.byref(h)) == wmdec.ERR_SHAPE and not h.value
+    cfg = wmdec.decoder_default_config()
+    cfg.act_dtype = wmdec.F32
+    assert l.decoder_create(ctypes.byref(cfg), ctypes.byref(h)) == wmdec.ERR_UNSUPPORTED
+    dec = wmdec.Decoder()
+    assert l.decoder_run(dec.handle, p, p, p, 9, None) == wmdec.ERR_INVALID_ARG
+    assert l.decoder_run(dec.handle, p, p, p, 1, None) == wmdec.ERR_WORKSPACE
+    dec.close()
+
+
+def test_synth_bf16_rounding_matches_torch():
+    import torch
+    x = np.random.default_rng(3).standard_normal(100000).astype(np.float32) * 37.0
+    x[:4] = [0.0, -0.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8]     # exact ties: to even
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    got = synth.bf16_round(x)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    bits = synth.bf16_bits(got)
+    assert np.array_equal(bits, torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16))
+
+
+def test_synth_is_deterministic_and_shaped():
+    a = synth.latent_sequence()
+    b = synth.latent_sequence()
+    assert a.shape == (4, 4, 60, 90) and np.array_equal(a, b)
+    # temporally correlated: consecutive differences are nearly the same step d
+    d1, d2 = a[1] - a[0], a[2] - a[1]
+    assert np.corrcoef(d1.ravel(), d2.ravel())[0, 1] > 0.95
+    z = synth.latent_single()
+    assert z.shape == (1, 4, 60, 90) and abs(float(z.std()) - 1.0) < 0.02
+    w = synth.decoder_weights()
+    assert abs(float(w["mid.res1.conv1.w"].std()) * np.sqrt(9 * 512) - 1.0) < 0.01
+    assert abs(float(w["conv_in.b"].std()) - 0.01) < 0.002
+    assert np.all(w["norm_out.gamma"] == 1) and np.all(w["norm_out.beta"] == 0)

@@ -1,0 +1,249 @@
+"""GPU parity: every per-op entry point of the C ABI against the fp64 oracle on
+the same seeded inputs, element by element.  Sizes span several tiles and a
+ragged tail; degenerate shapes included."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2602_00608_amd import synth, wmdec
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+def rng(seed):
+    return np.random.default_rng(synth.SEED_BASE + seed)
+
+
+# ------------------------------------------------------------------ a1: GroupNorm statistics
+@pytest.mark.parametrize("dtype,n,c,h,w,groups", [
+    ("f32", 1, 64, 32, 32, 32),      # workload 1 shape
+    ("f32", 2, 12, 5, 7, 4),         # general path, tiny
+    ("bf16", 1, 128, 37, 53, 32),    # 4 channels per group: one 16-byte vector spans two groups
+    ("bf16", 2, 256, 24, 36, 32),
+    ("f16", 1, 512, 15, 23, 32),     # 16 channels per group: a group spans two vectors
+    ("f16", 3, 24, 9, 11, 3),        # general path, 16 bit
+    ("f32", 1, 32, 1, 1, 32),        # one element per group: variance 0
+    ("bf16", 1, 128, 480, 720, 32),  # workload 3 size
+])
+def test_gn_stats(dtype, n, c, h, w, groups):
+    x = G.stored(rng(1).standard_normal((n, c, h, w)) * 1.7 + 0.6, dtype)
+    eps = 1e-6
+    mean, rstd = G.gn_stats(G.dev_nhwc(x, dtype), groups, eps)
+    wm, wr = ref.gn_stats(x, groups, eps)
+    gm, gr = mean.cpu().numpy().reshape(n, groups), rstd.cpu().numpy().reshape(n, groups)
+    sd = 1.0 / wr
+    assert np.max(np.abs(gm - wm) / sd) < 2e-5, np.max(np.abs(gm - wm) / sd)
+    assert np.max(np.abs(gr / wr - 1.0)) < 2e-5, np.max(np.abs(gr / wr - 1.0))
+
+
+def test_gn_stats_large_offset_no_cancellation():
+    # mean >> std: a naive E[x^2]-E[x]^2 in fp32 would lose the variance
+    x = (rng(2).standard_normal((1, 64, 40, 40)) * 0.01 + 100.0).astype(np.float32)
+    mean, rstd = G.gn_stats(G.dev_nhwc(x, "f32"), 32, 1e-6)
+    wm, wr = ref.gn_stats(x, 32, 1e-6)
+    assert np.max(np.abs(rstd.cpu().numpy() / wr.ravel() - 1.0)) < 1e-3
+    assert np.max(np.abs(mean.cpu().numpy() - wm.ravel())) < 1e-4
+
+
+def test_gn_stats_deterministic():
+    x = G.dev_nhwc(G.stored(rng(3).standard_normal((2, 128, 61, 47)), "bf16"), "bf16")
+    a = G.gn_stats(x, 32, 1e-6)
+    b = G.gn_stats(x, 32, 1e-6)
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+# ------------------------------------------------------------------ a3': nearest-2x upsample (bit exact)
+@pytest.mark.parametrize("dtype,n,c,h,w", [("bf16", 1, 256, 120, 180), ("f32", 2, 3, 5, 7), ("f16", 1, 8, 1, 1),
+                                           ("bf16", 2, 20, 6, 3), ("bf16", 1, 5, 4, 9)])
+def test_upsample2x_nearest_bit_exact(dtype, n, c, h, w):
+    x = G.stored(rng(4).standard_normal((n, c, h, w)), dtype)
+    xd = G.dev_nhwc(x, dtype)
+    y, check = G.canaried((n, 2 * h, 2 * w, c), G.TORCH[dtype])
+    wmdec.upsample2x_nearest(xd, y)
+    check()
+    want = ref.upsample2x(x)      # exact in fp64
+    got = G.host_nchw(y)
+    assert np.array_equal(got, want)
+
+
+# ------------------------------------------------------------------ layout conversion
+@pytest.mark.parametrize("sd,dd", [("f32", "f32"), ("f32", "bf16"), ("bf16", "f32"), ("f16", "f16")])
+def test_layout_roundtrip(sd, dd):
+    x = G.stored(G.stored(rng(5).standard_normal((2, 7, 33, 45)), sd), dd)   # representable in both
+    src = torch.from_numpy(x).to(G.TORCH[sd]).cuda()
+    nhwc = torch.empty((2, 33, 45, 7), dtype=G.TORCH[dd], device="cuda")
+    wmdec.nchw_to_nhwc(src, nhwc)
+    assert np.array_equal(G.host_nchw(nhwc), x.astype(np.float64))
+    back = torch.empty((2, 7, 33, 45), dtype=G.TORCH[sd], device="cuda")
+    wmdec.nhwc_to_nchw(nhwc, back)
+    assert torch.equal(back, src)
+
+
+# ------------------------------------------------------------------ a2/a4: fused norm -> SiLU -> conv3x3 (+bias, +residual)
+def run_conv(x, dtype, w, b, res, norm, silu, groups, ydtype, k=3, eps=1e-6, gamma=None, beta=None):
+    """x, res: float32 NCHW arrays of storable values; returns (gpu NCHW float64, oracle NCHW float64)."""
+    n, cin, h, wd = x.shape
+    cout = w.shape[0]
+    xd = G.dev_nhwc(x, dtype)
+    wp = G.pack(w, dtype)
+    wq = G.stored(w, dtype) if dtype != "f32" else w
+    y, check = G.canaried((n, h, wd, cout), G.TORCH[ydtype])
+    mean = rstd = gd = bd = None
+    if norm:
+        mean, rstd = G.gn_stats(xd, groups, eps)
+        gd, bd = G.dev_f32(gamma), G.dev_f32(beta)
+    fn = wmdec.gn_silu_conv3x3 if k == 3 else wmdec.gn_conv1x1
+    fn(xd, mean, rstd, gd, bd, groups, silu, wp, None if b is None else G.dev_f32(b),
+       None if res is None else G.dev_nhwc(res, dtype), y)
+    torch.cuda.synchronize()
+    check()
+    u = x.astype(np.float64)
+    if norm:
+        u = ref.group_norm(u, groups, eps, gamma, beta, apply_silu=silu)
+    want = ref.conv2d(u, wq, b)
+    if res is not None:
+        want = want + res
+    return G.host_nchw(y), want
+
+
+CONV_CASES = [
+    # dtype, ydtype, n, cin, cout, h, w, norm, silu, bias, residual
+    ("f32", "f32", 1, 64, 64, 32, 32, True, True, True, True),       # workload 1 conv
+    ("f32", "f32", 2, 4, 3, 5, 7, False, False, True, False),        # tiny, odd channels
+    ("f32", "f32", 1, 12, 20, 9, 10, True, True, False, True),
+    ("f32", "f32", 1, 8, 8, 1, 1, True, False, True, False),         # one pixel
+    ("bf16", "f32", 1, 128, 128, 40, 56, True, True, True, True),
+    ("bf16", "bf16", 2, 64, 96, 19, 21, True, True, True, True),
+    ("f16", "f16", 1, 256, 128, 17, 33, True, True, True, False),
+    ("f16", "f32", 1, 128, 3, 24, 31, True, True, True, False),      # conv_out shape class
+    ("bf16", "f32", 1, 4, 64, 12, 18, False, False, True, False),    # conv_in shape class
+    ("bf16", "f32", 1, 512, 512, 15, 23, True, True, True, True),
+    ("f16", "f32", 1, 32, 32, 64, 3, True, True, True, True),        # narrow image
+]
+
+
+@pytest.mark.parametrize("dtype,ydtype,n,cin,cout,h,w,norm,silu,bias,residual", CONV_CASES)
+def test_gn_silu_conv3x3(dtype, ydtype, n, cin, cout, h, w, norm, silu, bias, residual):
+    r = rng(10)
+    x = G.stored(r.standard_normal((n, cin, h, w)) * 1.3 + 0.2, dtype)
+    wt, b = synth.conv_params(r, cout, cin, 3, dtype != "f32")
+    res = G.stored(r.standard_normal((n, cout, h, w)), dtype) if residual else None
+    groups = 32 if cin % 32 == 0 else 4
+    gamma = (1 + 0.2 * r.standard_normal(cin)).astype(np.float32)
+    beta = (0.2 * r.standard_normal(cin)).astype(np.float32)
+    got, want = run_conv(x, dtype, wt, b if bias else None, res, norm, silu, groups, ydtype, gamma=gamma, beta=beta)
+    err = ref.rel_err(got, want)
+    tol = G.TOL[dtype]
+    assert err <= tol, err
+    if dtype != "f32" and ydtype == "f32":
+        assert err <= tol / 2, err   # fp32 output of 16-bit operands: well inside the bar
+
+
+def test_conv_padding_is_applied_after_activation():
+    # constant input, beta chosen so that SiLU(GN(x)) != 0: border outputs must see zeros, not SiLU(beta)
+    x = np.full((1, 32, 6, 6), 3.0, np.float32)
+    w = np.zeros((32, 32, 3, 3), np.float32)
+    w[:, :, :, :] = 1.0 / 32
+    gamma, beta = np.ones(32, np.float32), np.full(32, 2.0, np.float32)
+    got, want = run_conv(x, "f32", w, None, None, True, True, 32, "f32", gamma=gamma, beta=beta)
+    s = 2.0 / (1 + math.exp(-2.0))
+    assert abs(want[0, 0, 0, 0] - 4 * s) < 1e-12 and abs(want[0, 0, 2, 2] - 9 * s) < 1e-12
+    assert ref.rel_err(got, want) < 1e-5
+
+
+@pytest.mark.parametrize("dtype,ydtype,n,cin,cout,h,w,norm,residual", [
+    ("f32", "f32", 1, 24, 40, 7, 9, True, True),
+    ("bf16", "f32", 1, 512, 256, 24, 36, False, False),      # ResBlock shortcut shape class
+    ("f16", "f16", 2, 512, 1536, 5, 7, True, False),         # fused q,k,v projection shape class
+    ("bf16", "bf16", 1, 256, 128, 31, 17, False, True),
+])
+def test_gn_conv1x1(dtype, ydtype, n, cin, cout, h, w, norm, residual):
+    r = rng(11)
+    x = G.stored(r.standard_normal((n, cin, h, w)), dtype)
+    wt, b = synth.conv_params(r, cout, cin, 1, dtype != "f32")
+    res = G.stored(r.standard_normal((n, cout, h, w)), dtype) if residual else None
+    groups = 32 if cin % 32 == 0 else 4
+    gamma = (1 + 0.2 * r.standard_normal(cin)).astype(np.float32)
+    beta = (0.2 * r.standard_normal(cin)).astype(np.float32)
+    got, want = run_conv(x, dtype, wt, b, res, norm, False, groups, ydtype, k=1, gamma=gamma, beta=beta)
+    assert ref.rel_err(got, want) <= G.TOL[dtype]
+
+
+# ------------------------------------------------------------------ a3: upsample-conv
+@pytest.mark.parametrize("dtype,ydtype,n,cin,cout,h,w", [
+    ("f32", "f32", 1, 6, 10, 5, 7),
+    ("bf16", "f32", 1, 256, 256, 20, 28),
+    ("f16", "f16", 2, 128, 64, 9, 13),
+    ("bf16", "bf16", 1, 64, 64, 1, 1),
+])
+def test_upsample2x_conv3x3(dtype, ydtype, n, cin, cout, h, w):
+    r = rng(12)
+    x = G.stored(r.standard_normal((n, cin, h, w)), dtype)
+    wt, b = synth.conv_params(r, cout, cin, 3, dtype != "f32")
+    y, check = G.canaried((n, 2 * h, 2 * w, cout), G.TORCH[ydtype])
+    wmdec.upsample2x_conv3x3(G.dev_nhwc(x, dtype), G.pack(wt, dtype), G.dev_f32(b), y)
+    torch.cuda.synchronize()
+    check()
+    want = ref.upconv(x, G.stored(wt, dtype) if dtype != "f32" else wt, b)
+    assert ref.rel_err(G.host_nchw(y), want) <= G.TOL[dtype] / (2 if ydtype == "f32" else 1)
+
+
+def test_upconv_gather_index_map_bit_exact():
+    """One-hot kernels turn the fused upsample-conv into a pure gather: the output must equal the
+    shifted, zero-padded upsampled input bit for bit, for all nine taps."""
+    r = rng(13)
+    x = G.stored(r.standard_normal((1, 32, 7, 10)), "bf16")
+    up = np.pad(ref.upsample2x(x), ((0, 0), (0, 0), (1, 1), (1, 1)))
+    xd = G.dev_nhwc(x, "bf16")
+    for ky in range(3):
+        for kx in range(3):
+            w = np.zeros((32, 32, 3, 3), np.float32)
+            for c in range(32):
+                w[c, c, ky, kx] = 1.0
+            y = torch.empty((1, 14, 20, 32), dtype=torch.bfloat16, device="cuda")
+            wmdec.upsample2x_conv3x3(xd, G.pack(w, "bf16"), None, y)
+            assert np.array_equal(G.host_nchw(y), up[:, :, ky:ky + 14, kx:kx + 20]), (ky, kx)
+
+
+# ------------------------------------------------------------------ a5: attention block
+def run_attention(dtype, n, h, w, seed):
+    c, groups, eps = 512, 32, 1e-6
+    r = rng(seed)
+    x = G.stored(r.standard_normal((n, c, h, w)), dtype)
+    p = {"norm.gamma": (1 + 0.2 * r.standard_normal(c)).astype(np.float32),
+         "norm.beta": (0.2 * r.standard_normal(c)).astype(np.float32)}
+    for nm in ("q", "k", "v", "proj"):
+        p[nm + ".w"], p[nm + ".b"] = synth.conv_params(r, c, c, 1, True)
+    # sharpen the softmax a little so that it is not near-uniform
+    p["q.w"] = synth.bf16_round(p["q.w"] * 4.0)
+    p["k.w"] = synth.bf16_round(p["k.w"] * 4.0)
+    xd = G.dev_nhwc(x, dtype)
+    mean, rstd = G.gn_stats(xd, groups, eps)
+    wqkv = np.concatenate([p["q.w"], p["k.w"], p["v.w"]], axis=0)
+    bqkv = np.concatenate([p["q.b"], p["k.b"], p["v.b"]])
+    ws = torch.empty(wmdec.attention_workspace_bytes(n, h, w, c), dtype=torch.uint8, device="cuda")
+    y, check = G.canaried((n, h, w, c), G.TORCH[dtype])
+    wmdec.attention(xd, mean, rstd, G.dev_f32(p["norm.gamma"]), G.dev_f32(p["norm.beta"]), groups,
+                    G.pack(wqkv, dtype), G.dev_f32(bqkv), G.pack(p["proj.w"], dtype), G.dev_f32(p["proj.b"]), y, ws)
+    torch.cuda.synchronize()
+    check()
+    want = ref.attention_block(x, p, groups, eps)
+    return G.host_nchw(y), want, x
+
+
+@pytest.mark.parametrize("dtype,n,h,w", [("f16", 1, 5, 7), ("bf16", 2, 9, 8), ("f16", 1, 1, 1), ("bf16", 1, 16, 20)])
+def test_attention_small(dtype, n, h, w):
+    got, want, x = run_attention(dtype, n, h, w, 20)
+    assert ref.rel_err(got, want) <= G.TOL[dtype]
+    # the attention branch itself (output minus residual input) must agree too, not just x + small
+    assert ref.rel_err(got - x, want - x) <= 3 * G.TOL[dtype]
+
+
+def test_attention_full_size_5400_tokens():
+    got, want, x = run_attention("f16", 1, 60, 90, 21)
+    assert ref.rel_err(got, want) <= G.TOL["f16"]
+    assert ref.rel_err(got - x, want - x) <= 3 * G.TOL["f16"]
