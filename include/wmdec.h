@@ -65,11 +65,15 @@ int wmdec_gn_stats(const void* x, int x_dtype, int n, int h, int w, int c, int g
                    float* mean, float* rstd, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
- * Weight packing.  Convolution kernels read weights in the packed order
- * [ky][kx][cout][cin] (cin contiguous) in the operand type `op_dtype`
- * (F32 for the fp32 path, else BF16 or F16).  src is the logical
- * [cout][cin][k][k] tensor (k = 1 or 3) of src_dtype (F32 or BF16).
- * BF16 -> F16 conversion is exact for normal-range values.  */
+ * Weight packing.  Convolution kernels read weights in a packed order: per
+ * tap, fragments of 32 output x 16 input channels, each stored as 1 KiB (for
+ * 16-bit types) in the lane order of the matrix-core B operand, C_in padded to
+ * a multiple of 16 and C_out to a multiple of 32 with zeros, in the operand
+ * type `op_dtype` (F32 for the fp32 path, else BF16 or F16).  The layout is
+ * private to the library: always produce it with this call.  src is the
+ * logical [cout][cin][k][k] tensor (k = 1 or 3) of src_dtype (F32 or BF16).
+ * BF16 -> F16 conversion is exact for normal-range values.  `packed` must hold
+ * wmdec_conv_packed_bytes(...) bytes. */
 size_t wmdec_conv_packed_bytes(int cout, int cin, int k, int op_dtype);
 int wmdec_pack_conv_weights(const void* src, int src_dtype, int cout, int cin, int k,
                             void* packed, int op_dtype, void* stream);

@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "common.hpp"
+#include "pack_layout.hpp"
 
 namespace wmdec {
 
@@ -108,7 +109,7 @@ struct Builder {
     p.offset = off;
     off = align_up(off + p.bytes, 256);
     // packed: conv weights in the operand type, everything else copied as fp32
-    p.packed_bytes = dtype == WMDEC_F32 ? p.bytes : (size_t)s0 * s1 * s2 * s3 * dtype_size(d.cfg.act_dtype);
+    p.packed_bytes = dtype == WMDEC_F32 ? p.bytes : packed_elems(s2 * s3, s0, s1) * dtype_size(d.cfg.act_dtype);
     p.packed_offset = poff;
     poff = align_up(poff + p.packed_bytes, 256);
     d.params.push_back(p);
@@ -192,7 +193,7 @@ static int build_plan(wmdec_decoder& d) {
     B.conv_params("mid.attn.k", c0, c0, 1, &woff[1], &boff[1]);
     B.conv_params("mid.attn.v", c0, c0, 1, &woff[2], &boff[2]);
     // the packed blob also holds q, k, v fused into one [3c][c] matrix and one [3c] bias
-    d.qkv_w_off = B.poff; B.poff = align_up(B.poff + (size_t)3 * c0 * c0 * dtype_size(c.act_dtype), 256);
+    d.qkv_w_off = B.poff; B.poff = align_up(B.poff + packed_elems(1, 3 * c0, c0) * dtype_size(c.act_dtype), 256);
     d.qkv_b_off = B.poff; B.poff = align_up(B.poff + (size_t)3 * c0 * sizeof(float), 256);
     q.w_off = d.qkv_w_off;
     q.b_off = d.qkv_b_off;
@@ -310,7 +311,7 @@ int wmdec_gn_stats(const void* x, int x_dtype, int n, int h, int w, int c, int g
 
 size_t wmdec_conv_packed_bytes(int cout, int cin, int k, int op_dtype) {
   if (cout <= 0 || cin <= 0 || (k != 1 && k != 3) || !valid_dtype(op_dtype)) return 0;
-  return (size_t)k * k * cout * cin * dtype_size(op_dtype);
+  return packed_elems(k * k, cout, cin) * dtype_size(op_dtype);
 }
 
 int wmdec_pack_conv_weights(const void* src, int src_dtype, int cout, int cin, int k, void* packed, int op_dtype,

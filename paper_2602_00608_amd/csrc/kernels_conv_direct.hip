@@ -6,6 +6,7 @@
 // For 16-bit operand types the activated input is rounded to that type before
 // the product and accumulated in fp32, i.e. the arithmetic of the MFMA kernel.
 #include "common.hpp"
+#include "pack_layout.hpp"
 
 namespace wmdec {
 namespace {
@@ -49,7 +50,7 @@ struct DirectParams {
 __global__ __launch_bounds__(256) void conv_direct_kernel(DirectParams p) {
   __shared__ float s_in[(TH + 2) * HALO][KC + 1];
   __shared__ float s_w[9][KC][TCO];
-  __shared__ float s_scale[KC], s_shift[KC];
+  __shared__ float s_scale[KC], s_mean[KC], s_beta[KC];
 
   const int tid = threadIdx.x;
   const int tile = blockIdx.x;
@@ -60,6 +61,7 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(DirectParams p) {
   const int taps = p.ksize * p.ksize;
   const int h_in = p.upsample ? p.h / 2 : p.h, w_in = p.upsample ? p.w_out / 2 : p.w_out;
   const int cpg = p.mean ? p.cin / p.groups : 1;
+  const int cinb = packed_cin_blocks(p.cin), coutb = packed_cout_blocks(p.cout);
 
   // thread -> 4 pixels (one row segment) x 4 output channels
   const int pg = tid & 15, cg = tid >> 4;
@@ -75,20 +77,21 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(DirectParams p) {
     __syncthreads();
     if (tid < KC) {
       const int c = c0 + tid;
-      float sc = 1.f, sh = 0.f;
+      float sc = 1.f, mu = 0.f, be = 0.f;
       if (p.mean && c < p.cin) {
         const int g = c / cpg;
         sc = p.gamma[c] * p.rstd[n * p.groups + g];
-        sh = p.beta[c] - p.mean[n * p.groups + g] * sc;
+        mu = p.mean[n * p.groups + g];
+        be = p.beta[c];
       }
-      s_scale[tid] = sc; s_shift[tid] = sh;
+      s_scale[tid] = sc; s_mean[tid] = mu; s_beta[tid] = be;
     }
     // weights of this channel chunk: s_w[tap][k][co]
     for (int i = tid; i < taps * KC * TCO; i += 256) {
       const int k = i % KC, co = (i / KC) % TCO, tap = i / (KC * TCO);
       float v = 0.f;
       if (co0 + co < p.cout && c0 + k < p.cin)
-        v = load_as_float(p.w, p.op_dtype, ((size_t)tap * p.cout + co0 + co) * p.cin + c0 + k);
+        v = load_as_float(p.w, p.op_dtype, packed_index(tap, co0 + co, c0 + k, cinb, coutb));
       s_w[tap][k][co] = v;
     }
     __syncthreads();
@@ -105,7 +108,7 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(DirectParams p) {
                                     : (((size_t)n * h_in + sy) * w_in + sx) * p.cin + c;
         v = load_as_float(p.x, p.x_dtype, idx);
         if (p.mean) {
-          v = fmaf(v, s_scale[k], s_shift[k]);
+          v = fmaf(v - s_mean[k], s_scale[k], s_beta[k]);  // subtract first: no cancellation when |mean| >> std
           if (p.silu) v = silu_f(v);
         }
         v = round_op(v, p.op_dtype);

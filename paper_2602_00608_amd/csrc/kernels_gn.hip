@@ -194,7 +194,6 @@ Plan make_plan(int x_dtype, int n, int h, int w, int c, int groups) {
   // a vector must not straddle a group boundary unevenly: cpg | V or V | cpg
   p.vec = divisible && ((cpg % V == 0) || (V % cpg == 0));
   p.chunks = pick_chunks(pixels, c, V, p.vec);
-  if (n > 1 && p.chunks > 1024) p.chunks = 1024;
   p.chunk_pixels = (pixels + p.chunks - 1) / p.chunks;
   if (p.vec) {
     const int ppi = 256 / (c / V);

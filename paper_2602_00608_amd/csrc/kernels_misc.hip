@@ -1,6 +1,7 @@
 // Small data-movement kernels: nearest-2x upsample, weight packing, strided
 // transpose with type conversion (NCHW <-> NHWC, V -> V^T), fp32 copy.
 #include "common.hpp"
+#include "pack_layout.hpp"
 
 namespace wmdec {
 namespace {
@@ -33,17 +34,25 @@ __global__ __launch_bounds__(256) void upsample2x_elem(const T* __restrict__ x, 
   y[i] = x[((n * h_in + (oy >> 1)) * w_in + (ox >> 1)) * c + cc];
 }
 
-// dst[tap][row_off + co][ci] = convert(src[co][ci][tap])
+// One thread per element of the packed destination (see pack_layout.hpp).  Rows [row_off, row_off+cout)
+// of a destination with rows_total output channels are written from src[co][ci][tap]; padding elements
+// (ci >= cin or row >= rows_total) are zeroed; rows that belong to another source are left alone.
 template <typename S, typename D>
 __global__ __launch_bounds__(256) void pack_conv_kernel(const S* __restrict__ src, D* __restrict__ dst, int cout, int cin,
                                                         int taps, int row_off, int rows_total) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  const size_t total = (size_t)taps * cout * cin;
-  if (i >= total) return;
-  const int ci = (int)(i % cin);
-  const int co = (int)((i / cin) % cout);
-  const int tap = (int)(i / ((size_t)cin * cout));
-  dst[((size_t)tap * rows_total + row_off + co) * cin + ci] = from_float<D>(to_float(src[((size_t)co * cin + ci) * taps + tap]));
+  const int cinb = packed_cin_blocks(cin), coutb = packed_cout_blocks(rows_total);
+  if (i >= (size_t)taps * cinb * coutb * 512) return;
+  const int e = (int)(i & 7), lane = (int)((i >> 3) & 63);
+  size_t blk = i >> 9;
+  const int cob = (int)(blk % coutb); blk /= coutb;
+  const int cib = (int)(blk % cinb);
+  const int tap = (int)(blk / cinb);
+  const int row = cob * 32 + (lane & 31), ci = cib * 16 + (lane >> 5) * 8 + e;
+  if (ci >= cin || row >= rows_total) { dst[i] = from_float<D>(0.f); return; }
+  const int co = row - row_off;
+  if (co < 0 || co >= cout) return;
+  dst[i] = from_float<D>(to_float(src[((size_t)co * cin + ci) * taps + tap]));
 }
 
 // dst[b][i][j] = src[b][j][i], 32x32 tiles through LDS
@@ -72,7 +81,7 @@ __global__ __launch_bounds__(256) void copy_f32_kernel(const float* __restrict__
 
 template <typename S, typename D>
 int pack_t(const void* src, void* dst, int cout, int cin, int k, int row_off, int rows_total, hipStream_t s) {
-  const size_t total = (size_t)k * k * cout * cin;
+  const size_t total = packed_elems(k * k, rows_total, cin);
   hipLaunchKernelGGL((pack_conv_kernel<S, D>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
                      (const S*)src, (D*)dst, cout, cin, k * k, row_off, rows_total);
   WMDEC_HIP(hipGetLastError());

@@ -93,6 +93,7 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert l.wmdec_attention(p, 1, p, p, p, p, 32, p, p, p, p, 2 * p, 1, 4, 4, 512, p, 16, None) == wmdec.ERR_WORKSPACE
     assert l.wmdec_upsample2x_nearest(p, p, 1, 1, 2, 2, 8, None) == wmdec.ERR_INVALID_ARG
     assert l.wmdec_conv_packed_bytes(64, 64, 3, wmdec.F32) == 9 * 64 * 64 * 4
+    assert l.wmdec_conv_packed_bytes(3, 4, 3, wmdec.BF16) == 9 * 32 * 16 * 2   # padded to 32 x 16 fragments
     assert l.wmdec_conv_packed_bytes(64, 64, 2, wmdec.F32) == 0
     assert l.wmdec_status_string(wmdec.ERR_WORKSPACE) == b"workspace missing or too small"
     cfg = wmdec.decoder_default_config()
