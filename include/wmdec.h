@@ -207,6 +207,19 @@ int decoder_run(wmdec_decoder* dec, const void* latent, const void* packed, void
 int decoder_num_launches(const wmdec_decoder* dec);
 double decoder_flops_per_frame(const wmdec_decoder* dec);
 
+/* Per-step timing for measurement.  With profiling enabled decoder_run records
+ * a HIP event on `stream` before the first and after every step of the graph
+ * (a step = one GroupNorm statistics pass, one convolution, the V transpose or
+ * the attention core).  decoder_step_info gives, for step `index`, the kernel
+ * family that executes it and its algorithmic FLOPs and HBM bytes per frame
+ * (every input, residual, output and weight tensor counted once: the Eq. 9
+ * accounting).  decoder_step_times waits for the last profiled decoder_run and
+ * returns the elapsed milliseconds of each step (count = decoder_num_steps). */
+int decoder_set_profiling(wmdec_decoder* dec, int enable);
+int decoder_num_steps(const wmdec_decoder* dec);
+int decoder_step_info(const wmdec_decoder* dec, int index, const char** kernel, double* flops, double* bytes);
+int decoder_step_times(const wmdec_decoder* dec, float* ms, int count);
+
 #ifdef __cplusplus
 }
 #endif

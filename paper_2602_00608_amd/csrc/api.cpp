@@ -32,6 +32,11 @@ int launch_conv(const ConvArgs& a, hipStream_t s) {
   return launch_conv_direct(a, s);
 }
 
+const char* conv_kernel_label(const ConvArgs& a) {
+  if (!conv_mfma_supported(a)) return "conv_direct";
+  return a.ksize == 3 ? "conv_mfma_3x3" : "conv_mfma_1x1";
+}
+
 static inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -73,6 +78,7 @@ struct Step {
   int ksize = 3, upsample = 0, norm = 0, silu = 0;
   int x_nchw = 0, y_nchw = 0, to_attn = 0 /*1: dst is the qkv buffer, 2: src is the attention output*/;
   size_t w_off = 0, b_off = 0, gamma_off = 0, beta_off = 0;
+  double flops = 0.0, bytes = 0.0;   // algorithmic work / HBM traffic of this step for one frame
 };
 
 }  // namespace wmdec
@@ -91,6 +97,12 @@ struct wmdec_decoder {
   int launches = 0;
   void* ws = nullptr;
   size_t ws_bytes = 0;
+  bool profiling = false;
+  int profiled_batch = 0;
+  std::vector<hipEvent_t> events;   // steps.size() + 1 when profiling was ever enabled
+  ~wmdec_decoder() {
+    for (hipEvent_t e : events) (void)hipEventDestroy(e);
+  }
 };
 
 namespace wmdec {
@@ -130,11 +142,21 @@ struct Builder {
   }
   void stats(int src, int h, int w, int c) {
     Step s; s.kind = Step::STATS; s.src = src; s.h = h; s.w = w; s.cin = c;
+    s.bytes = (double)h * w * c * dtype_size(d.cfg.act_dtype);
     d.steps.push_back(s);
     d.launches += 2;
   }
-  void count_conv(const Step& s) {
-    d.flops += 2.0 * s.ksize * s.ksize * (double)s.cin * s.cout * (double)s.h * s.w;
+  // call right after pushing a CONV step: accounts its work on the pushed copy
+  void count_conv(const Step&) {
+    Step& s = d.steps.back();
+    const double es = (double)dtype_size(d.cfg.act_dtype);
+    const double px_out = (double)s.h * s.w, px_in = s.upsample ? px_out / 4 : px_out;
+    s.flops = 2.0 * s.ksize * s.ksize * (double)s.cin * s.cout * px_out;
+    s.bytes = px_in * s.cin * (s.src == BUF_LATENT ? 2.0 : es)                  // input, once
+              + px_out * s.cout * (s.dst == BUF_OUT ? 4.0 : es)                 // output, once
+              + (s.res != BUF_NONE ? px_out * s.cout * es : 0.0)                // residual, once
+              + (double)s.ksize * s.ksize * s.cin * s.cout * es;                // weights, once
+    d.flops += s.flops;
     d.launches += 1;
   }
   void track(int h, int w, int c) {
@@ -200,10 +222,13 @@ static int build_plan(wmdec_decoder& d) {
     B.stats(cur, h, w, c0);
     d.steps.push_back(q); B.count_conv(q);
     Step tv; tv.kind = Step::QKV_TRANSPOSE_V; tv.h = h; tv.w = w; tv.cin = c0;
+    tv.bytes = 2.0 * h * w * c0 * dtype_size(c.act_dtype);
     d.steps.push_back(tv); d.launches += 1;
     Step f; f.kind = Step::FLASH; f.h = h; f.w = w; f.cin = c0;
+    f.flops = 4.0 * (double)(h * w) * (double)(h * w) * c0;
+    f.bytes = 4.0 * h * w * c0 * dtype_size(c.act_dtype);
     d.steps.push_back(f); d.launches += 1;
-    d.flops += 4.0 * (double)(h * w) * (double)(h * w) * c0;
+    d.flops += f.flops;
     Step p; p.kind = Step::CONV; p.to_attn = 2; p.dst = other(1); p.res = cur; p.h = h; p.w = w; p.cin = c0; p.cout = c0; p.ksize = 1;
     B.conv_params("mid.attn.proj", c0, c0, 1, &p.w_off, &p.b_off);
     d.steps.push_back(p); B.count_conv(p);
@@ -579,6 +604,9 @@ int decoder_run(wmdec_decoder* dec, const void* latent, const void* packed, void
   float* mean = (float*)(ws + L.mean);
   float* rstd = (float*)(ws + L.rstd);
   auto buf = [&](int id) -> void* { return id >= 0 ? (void*)(ws + L.act[id]) : nullptr; };
+  const bool prof = dec->profiling;
+  if (prof) { dec->profiled_batch = batch; WMDEC_HIP(hipEventRecord(dec->events[0], s)); }
+  size_t step_index = 0;
   for (const Step& st : dec->steps) {
     int rc = WMDEC_OK;
     switch (st.kind) {
@@ -619,7 +647,59 @@ int decoder_run(wmdec_decoder* dec, const void* latent, const void* packed, void
       }
     }
     if (rc != WMDEC_OK) return rc;
+    ++step_index;
+    if (prof) WMDEC_HIP(hipEventRecord(dec->events[step_index], s));
   }
+  return WMDEC_OK;
+}
+
+int decoder_set_profiling(wmdec_decoder* dec, int enable) {
+  WMDEC_REQUIRE(dec, WMDEC_ERR_INVALID_ARG, "decoder_set_profiling: null decoder");
+  if (enable && dec->events.empty()) {
+    for (size_t i = 0; i <= dec->steps.size(); ++i) {
+      hipEvent_t e;
+      WMDEC_HIP(hipEventCreate(&e));
+      dec->events.push_back(e);
+    }
+  }
+  dec->profiling = enable != 0;
+  return WMDEC_OK;
+}
+
+int decoder_num_steps(const wmdec_decoder* dec) { return dec ? (int)dec->steps.size() : 0; }
+
+int decoder_step_info(const wmdec_decoder* dec, int index, const char** kernel, double* flops, double* bytes) {
+  WMDEC_REQUIRE(dec, WMDEC_ERR_INVALID_ARG, "decoder_step_info: null decoder");
+  WMDEC_REQUIRE(index >= 0 && index < (int)dec->steps.size(), WMDEC_ERR_INVALID_ARG, "decoder_step_info: index %d out of range", index);
+  const Step& st = dec->steps[index];
+  if (flops) *flops = st.flops;
+  if (bytes) *bytes = st.bytes;
+  if (kernel) {
+    switch (st.kind) {
+      case Step::STATS: *kernel = "gn_stats"; break;
+      case Step::QKV_TRANSPOSE_V: *kernel = "transpose"; break;
+      case Step::FLASH: *kernel = "flash_attn"; break;
+      case Step::CONV: {
+        ConvArgs a;   // only the fields the kernel choice looks at
+        a.op_dtype = dec->cfg.act_dtype; a.res_dtype = a.op_dtype;
+        a.x_dtype = st.src == BUF_LATENT ? (int)WMDEC_BF16 : a.op_dtype; a.x_nchw = st.x_nchw;
+        a.y_dtype = st.dst == BUF_OUT ? (int)WMDEC_F32 : a.op_dtype; a.y_nchw = st.y_nchw;
+        a.n = 1; a.h = st.h; a.w = st.w; a.cin = st.cin; a.cout = st.cout; a.ksize = st.ksize; a.upsample = st.upsample;
+        *kernel = conv_kernel_label(a);
+        break;
+      }
+    }
+  }
+  return WMDEC_OK;
+}
+
+int decoder_step_times(const wmdec_decoder* dec, float* ms, int count) {
+  WMDEC_REQUIRE(dec && ms, WMDEC_ERR_INVALID_ARG, "decoder_step_times: null pointer");
+  WMDEC_REQUIRE(dec->profiling && dec->profiled_batch > 0, WMDEC_ERR_INVALID_ARG,
+                "decoder_step_times: no profiled decoder_run has been enqueued");
+  WMDEC_REQUIRE(count == (int)dec->steps.size(), WMDEC_ERR_INVALID_ARG, "decoder_step_times: count must be %zu", dec->steps.size());
+  WMDEC_HIP(hipEventSynchronize(dec->events.back()));
+  for (int i = 0; i < count; ++i) WMDEC_HIP(hipEventElapsedTime(&ms[i], dec->events[i], dec->events[i + 1]));
   return WMDEC_OK;
 }
 

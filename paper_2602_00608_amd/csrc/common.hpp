@@ -97,6 +97,7 @@ bool conv_mfma_supported(const ConvArgs& a);
 int launch_conv_mfma(const ConvArgs& a, hipStream_t s);
 // picks the kernel
 int launch_conv(const ConvArgs& a, hipStream_t s);
+const char* conv_kernel_label(const ConvArgs& a);
 
 // kernels_gn.hip
 size_t gn_stats_workspace_bytes(int n, int h, int w, int c, int groups);

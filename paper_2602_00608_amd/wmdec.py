@@ -64,6 +64,11 @@ SIGNATURES = {
     "decoder_run": (_i, [_vp, _vp, _vp, _vp, _i, _vp]),
     "decoder_num_launches": (_i, [_vp]),
     "decoder_flops_per_frame": (ctypes.c_double, [_vp]),
+    "decoder_set_profiling": (_i, [_vp, _i]),
+    "decoder_num_steps": (_i, [_vp]),
+    "decoder_step_info": (_i, [_vp, _i, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_double),
+                               ctypes.POINTER(ctypes.c_double)]),
+    "decoder_step_times": (_i, [_vp, ctypes.POINTER(ctypes.c_float), _i]),
 }
 
 _lib = None
@@ -244,6 +249,25 @@ class Decoder:
     def set_workspace(self, workspace):
         self._workspace = workspace  # keep the tensor alive
         _check(lib().decoder_set_workspace(self.handle, _ptr(workspace), workspace.numel() * workspace.element_size()))
+
+    def set_profiling(self, enable):
+        _check(lib().decoder_set_profiling(self.handle, int(enable)))
+
+    def step_info(self):
+        """[(kernel family, algorithmic flops per frame, algorithmic bytes per frame)] per graph step."""
+        out = []
+        for i in range(lib().decoder_num_steps(self.handle)):
+            k, fl, by = ctypes.c_char_p(), ctypes.c_double(), ctypes.c_double()
+            _check(lib().decoder_step_info(self.handle, i, ctypes.byref(k), ctypes.byref(fl), ctypes.byref(by)))
+            out.append((k.value.decode(), fl.value, by.value))
+        return out
+
+    def step_times(self):
+        """Milliseconds of every step of the last profiled run (synchronises on its last event)."""
+        n = lib().decoder_num_steps(self.handle)
+        ms = (ctypes.c_float * n)()
+        _check(lib().decoder_step_times(self.handle, ms, n))
+        return list(ms)
 
     def run(self, latent, packed, out):
         _check(lib().decoder_run(self.handle, _ptr(latent), _ptr(packed), _ptr(out), latent.shape[0], _stream()))
