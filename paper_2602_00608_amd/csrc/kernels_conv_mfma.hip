@@ -23,6 +23,7 @@ namespace wmdec {
 namespace {
 
 int g_dbg = 0;
+int g_tile = -1;
 int g_variant = 0;   // kernel variant under evaluation (set from WMDEC_CONV_VARIANT at first launch)
 
 struct MfmaParams {
@@ -32,6 +33,7 @@ struct MfmaParams {
   int n, h, w_out, cin, cout, upsample;
   int tiles_x, tiles_y, ntiles, total;
   int cin_blocks, cout_blocks;   // packed-layout extents: ceil(cin/16), ceil(cout/32)
+  int y_nchw;                    // 1: y is planar [n][cout][h][w] (the frame), else NHWC
   int dbg;                       // ablation switches for timing experiments (0 in production)
 };
 
@@ -51,8 +53,29 @@ template <typename T> __device__ __forceinline__ void unpack8(const u32x4& v, fl
 template <typename T, typename TO, int MI, int NI, int MTW, int MTH, int MT_PER_ROW>
 __device__ __forceinline__ void epilogue_store(const f32x16 (&acc)[MI][NI], float* lds, int lane, int mt0, int ty0,
                                                int tx0, int co_w, const float* bias, const T* rin, TO* yout, int h,
-                                               int w_out, int cout, bool skip) {
+                                               int w_out, int cout, bool skip, bool nchw) {
   constexpr int RW = NI * 32 + 4;       // padded row of the patch, floats
+  if (nchw) {
+    // planar output with few channels (the frame): a lane owns one pixel of the M tile and walks the
+    // channels, so that 32 lanes write 32 consecutive pixels of one plane
+    const int lm = lane & 31, lk = lane >> 5;
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+      const int mt = mt0 + mi;
+      const int oy = ty0 + (mt / MT_PER_ROW) * MTH + lm / MTW, ox = tx0 + (mt % MT_PER_ROW) * MTW + lm % MTW;
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) lds[(8 * (r / 4) + 4 * lk + (r % 4)) * RW + ni * 32 + lm] = acc[mi][ni][r];
+      if (oy < h && ox < w_out && !skip) {
+        for (int c = lk; c < NI * 32 && co_w + c < cout; c += 2) {
+          const float v = lds[lm * RW + c] + (bias ? bias[co_w + c] : 0.f);
+          yout[((size_t)(co_w + c) * h + oy) * w_out + ox] = from_float<TO>(v);
+        }
+      }
+    }
+    return;
+  }
   constexpr int VPL = 2 * NI;           // 8-channel vectors per lane per M tile (32 pixels x NI*4 vectors / 64 lanes)
   const int lm = lane & 31, lk = lane >> 5;
   const int cvec = lane % (NI * 4);     // which 8-channel vector of the row this lane reads back
@@ -271,7 +294,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p) {
   const T* rin = p.res ? reinterpret_cast<const T*>(p.res) + (size_t)n * p.h * p.w_out * p.cout : nullptr;
   float* patch = reinterpret_cast<float*>(smem) + wave * (32 * (NI * 32 + 4));
   epilogue_store<T, TO, MI, NI, MTW, MTH, MT_PER_ROW>(acc, patch, lane, wm * MI, ty0, tx0, co0 + wn * NI * 32, p.bias, rin,
-                                                      yout, p.h, p.w_out, p.cout, (p.dbg & 4) != 0);
+                                                      yout, p.h, p.w_out, p.cout, (p.dbg & 4) != 0, p.y_nchw != 0);
 }
 
 // ---------------------------------------------------------------------------
@@ -368,7 +391,7 @@ __global__ __launch_bounds__(512, 1) void conv_ws_kernel(MfmaParams p) {
       const T* rin = p.res ? reinterpret_cast<const T*>(p.res) + (size_t)n * p.h * p.w_out * p.cout : nullptr;
       float* patch = reinterpret_cast<float*>(smem + 2 * HP * PS * 2) + wave * (32 * (NI * 32 + 4));
       epilogue_store<T, TO, MI, NI, MTW, MTH, MT_PER_ROW>(acc, patch, lane, wm * MI, ty0, tx0, co0 + wn * NI * 32, p.bias,
-                                                          rin, yout, p.h, p.w_out, p.cout, (p.dbg & 4) != 0);
+                                                          rin, yout, p.h, p.w_out, p.cout, (p.dbg & 4) != 0, p.y_nchw != 0);
     }
   } else {
     // ------------------------------------------------------------ producers
@@ -460,9 +483,9 @@ int launch_ws(const ConvArgs& a, hipStream_t s) {
   p.w = a.wt; p.bias = a.bias; p.res = a.res; p.y = a.y;
   p.silu = a.silu; p.groups = a.groups; p.norm = a.mean != nullptr;
   p.n = a.n; p.h = a.h; p.w_out = a.w; p.cin = a.cin; p.cout = a.cout; p.upsample = a.upsample;
-  p.tiles_x = (a.w + TW - 1) / TW; p.tiles_y = (a.h + TH - 1) / TH; p.ntiles = a.cout / TN;
+  p.tiles_x = (a.w + TW - 1) / TW; p.tiles_y = (a.h + TH - 1) / TH; p.ntiles = (a.cout + TN - 1) / TN;
   p.total = p.tiles_x * p.tiles_y * p.ntiles * a.n;
-  p.cin_blocks = packed_cin_blocks(a.cin); p.cout_blocks = packed_cout_blocks(a.cout); p.dbg = g_dbg;
+  p.cin_blocks = packed_cin_blocks(a.cin); p.cout_blocks = packed_cout_blocks(a.cout); p.dbg = g_dbg; p.y_nchw = a.y_nchw;
   const size_t smem = (size_t)2 * HP * (KC + 8) * 2 + (size_t)4 * 32 * (NI * 32 + 4) * sizeof(float);
   auto kern = conv_ws_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC>;
   static bool attr_set = false;
@@ -486,16 +509,16 @@ int launch_cfg(const ConvArgs& a, hipStream_t s) {
   p.w = a.wt; p.bias = a.bias; p.res = a.res; p.y = a.y;
   p.silu = a.silu; p.groups = a.groups; p.norm = a.mean != nullptr;
   p.n = a.n; p.h = a.h; p.w_out = a.w; p.cin = a.cin; p.cout = a.cout; p.upsample = a.upsample;
-  p.tiles_x = (a.w + TW - 1) / TW; p.tiles_y = (a.h + TH - 1) / TH; p.ntiles = a.cout / TN;
+  p.tiles_x = (a.w + TW - 1) / TW; p.tiles_y = (a.h + TH - 1) / TH; p.ntiles = (a.cout + TN - 1) / TN;
   p.total = p.tiles_x * p.tiles_y * p.ntiles * a.n;
-  p.cin_blocks = packed_cin_blocks(a.cin); p.cout_blocks = packed_cout_blocks(a.cout); p.dbg = g_dbg;
+  p.cin_blocks = packed_cin_blocks(a.cin); p.cout_blocks = packed_cout_blocks(a.cout); p.dbg = g_dbg; p.y_nchw = a.y_nchw;
   size_t smem = (((size_t)HP * (KC + 8) * 2 + 15) & ~(size_t)15) + (size_t)a.cin * sizeof(float2);
   const size_t patch = (size_t)4 * 32 * (NI * 32 + 4) * sizeof(float);   // epilogue patches of the four wavefronts
   if (smem < patch) smem = patch;
   auto kern = conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC>;
   static bool attr_set = false;   // per instantiation
   if (!attr_set) {
-    WMDEC_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024));
+    WMDEC_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024));   // two workgroups per compute unit
     attr_set = true;
   }
   hipLaunchKernelGGL(kern, dim3((unsigned)p.total), dim3(256), smem, s, p);
@@ -510,6 +533,21 @@ int launch_shape(const ConvArgs& a, hipStream_t s) {
   }
   // tile choice: 256 pixels x 128 channels when that still gives every compute unit work, else smaller
   const long px = (long)a.n * a.h * a.w;
+  if (a.cout <= 32) return launch_cfg<T, TO, 8, 32, 4, 1, 1, KS, 32>(a, s);   // few output channels (the frame): one 32-wide tile
+  if (g_tile >= 0) {   // tile sweep
+    const bool n128 = a.cout % 128 == 0;
+    switch (g_tile) {
+      case 0: if (n128) return launch_cfg<T, TO, 8, 32, 2, 2, 2, KS, 32>(a, s); break;   // 256 x 128
+      case 1: if (n128) return launch_cfg<T, TO, 4, 32, 2, 2, 2, KS, 32>(a, s); break;   // 128 x 128
+      case 2: return launch_cfg<T, TO, 4, 32, 4, 1, 2, KS, 32>(a, s);                    // 128 x 64
+      case 3: return launch_cfg<T, TO, 8, 32, 4, 1, 2, KS, 32>(a, s);                    // 256 x 64
+      case 4: if (n128) return launch_cfg<T, TO, 8, 16, 2, 2, 2, KS, 32>(a, s); break;   // 128 x 128, 8x16 patch
+      case 5: if (n128) return launch_cfg<T, TO, 16, 16, 2, 2, 2, KS, 32>(a, s); break;  // 256 x 128, 16x16 patch
+      case 6: return launch_cfg<T, TO, 8, 16, 4, 1, 2, KS, 32>(a, s);                    // 128 x 64, 8x16 patch
+      case 7: if (n128) return launch_cfg<T, TO, 8, 32, 2, 2, 2, KS, 64>(a, s); break;   // 256 x 128, 64-channel chunks
+      default: break;
+    }
+  }
   if (a.cout % 128 == 0 && px * (a.cout / 128) >= 256L * 256 * 3) return launch_cfg<T, TO, 8, 32, 2, 2, 2, KS, 32>(a, s);
   if (a.cout % 128 == 0 && px * (a.cout / 128) >= 128L * 256 * 3) return launch_cfg<T, TO, 4, 32, 2, 2, 2, KS, 32>(a, s);
   return launch_cfg<T, TO, 4, 32, 4, 1, 2, KS, 32>(a, s);   // 128 pixels x 64 channels
@@ -528,8 +566,10 @@ bool conv_mfma_supported(const ConvArgs& a) {
   if (!is_16bit(a.op_dtype) || a.x_dtype != a.op_dtype) return false;
   if (a.res && a.res_dtype != a.op_dtype) return false;
   if (a.y_dtype != a.op_dtype && a.y_dtype != WMDEC_F32) return false;
-  if (a.x_nchw || a.y_nchw) return false;
-  if (a.cin % 32 != 0 || a.cout % 64 != 0) return false;
+  if (a.x_nchw) return false;
+  if (a.y_nchw && !(a.cout <= 32 && a.y_dtype == WMDEC_F32 && !a.res)) return false;
+  if (a.cin % 32 != 0) return false;
+  if (a.cout % 64 != 0 && !(a.y_nchw && a.cout <= 32)) return false;
   if (a.cin > 4096) return false;   // scale/shift table lives in LDS
   if (a.ksize != 1 && a.ksize != 3) return false;
   return true;
@@ -537,7 +577,7 @@ bool conv_mfma_supported(const ConvArgs& a) {
 
 int launch_conv_mfma(const ConvArgs& a, hipStream_t s) {
   static bool init = false;
-  if (!init) { const char* e = getenv("WMDEC_CONV_VARIANT"); g_variant = e ? atoi(e) : 0; const char* d = getenv("WMDEC_CONV_DBG"); g_dbg = d ? atoi(d) : 0; init = true; }
+  if (!init) { const char* e = getenv("WMDEC_CONV_VARIANT"); g_variant = e ? atoi(e) : 0; const char* d = getenv("WMDEC_CONV_DBG"); g_dbg = d ? atoi(d) : 0; const char* t = getenv("WMDEC_CONV_TILE"); g_tile = t ? atoi(t) : -1; init = true; }
   return a.op_dtype == WMDEC_BF16 ? launch_type<bf16_t>(a, s) : launch_type<f16_t>(a, s);
 }
 
