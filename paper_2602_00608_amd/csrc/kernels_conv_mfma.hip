@@ -92,27 +92,25 @@ __device__ __forceinline__ void epilogue_store(const f32x16 (&acc)[MI][NI], floa
   float bv[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) bv[e] = bias ? bias[co_w + cvec * 8 + e] : 0.f;
-  // residual vectors of all M tiles first (unconditional loads, clamped to element 0 outside the image):
-  // their latency is paid once and hides behind the LDS round trips
-  u32x4 rv[RES ? MI : 1][VPL];
+  // 32-bit element offset of this lane's vector in M tile mi, row j (or -1 outside the image)
+  auto vec_off = [&](int mi, int j) -> int {
+    const int mt = mt0 + mi;
+    const int pi = prow + j * (64 / (NI * 4));
+    const int oy = ty0 + (mt / MT_PER_ROW) * MTH + pi / MTW, ox = tx0 + (mt % MT_PER_ROW) * MTW + pi % MTW;
+    return (oy < h && ox < w_out) ? (oy * w_out + ox) * cout + co_w + cvec * 8 : -1;   // < 2^30 elements (checked on the host)
+  };
+  // residual vectors are fetched two M tiles ahead (unconditional loads, clamped to element 0 outside the
+  // image) so that their latency hides behind the LDS round trips of the tiles before
+  constexpr int RD = 2;
+  u32x4 rv[RD][VPL];
   if constexpr (RES) {
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi) {
-      const int mt = mt0 + mi;
-      const int py0 = ty0 + (mt / MT_PER_ROW) * MTH, px0 = tx0 + (mt % MT_PER_ROW) * MTW;
+    for (int mi = 0; mi < RD && mi < MI; ++mi)
 #pragma unroll
-      for (int j = 0; j < VPL; ++j) {
-        const int pi = prow + j * (64 / (NI * 4));
-        const int oy = py0 + pi / MTW, ox = px0 + pi % MTW;
-        const bool ok = oy < h && ox < w_out;
-        rv[mi][j] = *reinterpret_cast<const u32x4*>(rin + (ok ? ((size_t)oy * w_out + ox) * cout + co_w + cvec * 8 : 0));
-      }
-    }
+      for (int j = 0; j < VPL; ++j) rv[mi][j] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(rin) + (unsigned)(max(vec_off(mi, j), 0) * (int)sizeof(T)));
   }
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) {
-    const int mt = mt0 + mi;
-    const int py0 = ty0 + (mt / MT_PER_ROW) * MTH, px0 = tx0 + (mt % MT_PER_ROW) * MTW;
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
@@ -120,19 +118,21 @@ __device__ __forceinline__ void epilogue_store(const f32x16 (&acc)[MI][NI], floa
 #pragma unroll
     for (int j = 0; j < VPL; ++j) {
       const int pi = prow + j * (64 / (NI * 4));
-      const int oy = py0 + pi / MTW, ox = px0 + pi % MTW;
+      const int off = vec_off(mi, j);
       const f32x4 lo = *reinterpret_cast<const f32x4*>(lds + pi * RW + cvec * 8);
       const f32x4 hi = *reinterpret_cast<const f32x4*>(lds + pi * RW + cvec * 8 + 4);
       float v[8] = {lo[0] + bv[0], lo[1] + bv[1], lo[2] + bv[2], lo[3] + bv[3],
                     hi[0] + bv[4], hi[1] + bv[5], hi[2] + bv[6], hi[3] + bv[7]};
       if constexpr (RES) {
         float rf[8];
-        unpack8<T>(rv[mi][j], rf);
+        unpack8<T>(rv[mi % RD][j], rf);
 #pragma unroll
         for (int e = 0; e < 8; ++e) v[e] += rf[e];
+        if (mi + RD < MI)
+          rv[mi % RD][j] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(rin) + (unsigned)(max(vec_off(mi + RD, j), 0) * (int)sizeof(T)));
       }
-      if (oy < h && ox < w_out) {
-        TO* dst = yout + ((size_t)oy * w_out + ox) * cout + co_w + cvec * 8;
+      if (off >= 0) {
+        TO* dst = reinterpret_cast<TO*>(reinterpret_cast<char*>(yout) + (unsigned)(off * (int)sizeof(TO)));
         if constexpr (sizeof(TO) == 4) {
           reinterpret_cast<f32x4*>(dst)[0] = f32x4{v[0], v[1], v[2], v[3]};
           reinterpret_cast<f32x4*>(dst)[1] = f32x4{v[4], v[5], v[6], v[7]};
@@ -206,7 +206,8 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p) {
   T* s_a = reinterpret_cast<T*>(smem);                                          // [2][HP][PS]
   float2* s_ab = reinterpret_cast<float2*>(smem + ((2 * BUF * 2 + 15) & ~15));  // [cin] (scale, shift)
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform: keeps the per-wave addresses scalar
   const int wm = wave / WN, wn = wave % WN;
   const int lm = lane & 31, lk = lane >> 5;
 
@@ -264,8 +265,8 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p) {
 
   // ---- staging: a thread owns NV (pixel, channel-octet) vectors of the halo tile; the octet is the same for all
   const int cvec = tid % VPP;
-  const T* xin = reinterpret_cast<const T*>(p.x) + (size_t)n * h_in * w_in * p.cin + cvec * 8;
-  int src_off[NV];          // element offset of the vector's pixel in x, or -1: outside the image / past the tile
+  const char* xin = reinterpret_cast<const char*>(p.x) + (size_t)n * h_in * w_in * p.cin * sizeof(T);   // uniform base
+  int src_off[NV];          // byte offset of the vector in x (chunk 0), or -1: outside the image / past the tile
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     const int v = tid + i * 256;
@@ -275,17 +276,22 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p) {
     src_off[i] = -1;
     if (v < HP * VPP && gy >= 0 && gy < p.h && gx >= 0 && gx < p.w_out) {
       const int sy = p.upsample ? gy >> 1 : gy, sx = p.upsample ? gx >> 1 : gx;
-      src_off[i] = (sy * w_in + sx) * p.cin;
+      src_off[i] = ((sy * w_in + sx) * p.cin + cvec * 8) * (int)sizeof(T);
     }
   }
-  u32x4 raw[NV];
-  // Global loads of chunk c0 into registers.  Unconditional (vectors outside the image read pixel 0 and are
-  // zeroed at activation): a load under a lane mask makes the compiler wait for it at the end of the branch.
-  auto issue = [&](int c0) {
+  // Two register sets of raw vectors: chunk k travels in set k & 1.  The loads of chunk k+2 are issued right
+  // after the MFMA sweep of chunk k, in front of the activation of chunk k+1: vector-memory loads return in
+  // order, so weight-fragment loads issued behind a batch of activation loads cannot be consumed before that
+  // batch has landed, and the activation phase is the one stretch in which no weight fragment is awaited.
+  u32x4 raw0[NV], raw1[NV];
+  // Unconditional loads (vectors outside the image read pixel 0 and are zeroed at activation): a load under
+  // a lane mask makes the compiler wait for it at the end of the branch.
+  auto issue = [&](u32x4 (&raw)[NV], int chunk) {
+    const int cb = min(chunk, p.cin / KC - 1) * KC * (int)sizeof(T);   // past the last chunk: a harmless reload
 #pragma unroll
-    for (int i = 0; i < NV; ++i) raw[i] = *reinterpret_cast<const u32x4*>(xin + max(src_off[i], 0) + c0);
+    for (int i = 0; i < NV; ++i) raw[i] = *reinterpret_cast<const u32x4*>(xin + (unsigned)(max(src_off[i], 0) + cb));
   };
-  auto activate = [&](int c0, T* buf) {   // scale/shift + SiLU + store into the staged tile
+  auto activate = [&](const u32x4 (&raw)[NV], int c0, T* buf) {   // scale/shift + SiLU + store into the staged tile
     float sc[8], sh[8];
     if (p.norm) {
 #pragma unroll
@@ -310,27 +316,32 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p) {
       }
     }
   };
-
-  TRACE(0);
-  issue(0);
-  __syncthreads();            // scale/shift table complete
-  activate(0, s_a);
-  __syncthreads();
-  TRACE(1);
   const int nchunks = p.cin / KC;
-  for (int c = 0; c < nchunks; ++c) {
+  // one chunk: MFMA sweep of buffer c & 1, loads of chunk c+2 into the set just freed, activation of chunk c+1
+  auto chunk_step = [&](int c, u32x4 (&mine)[NV], const u32x4 (&next)[NV]) {
     const bool more = c + 1 < nchunks;
-    TRACE(40 + c);
-    if (more) issue((c + 1) * KC);          // lands while the matrix cores work on chunk c
     const u32x4* bcur = wcol + (size_t)(c * KK) * kk_stride;
     const u32x4* bnext = more ? bcur + (size_t)KK * kk_stride : bcur;
     TRACE(2 + 4 * c);
     mfma_chunk<T, MI, NI, KS, KC, HW_, PS, D>(s_a + (c & 1) * BUF, a_off, bcur, bnext, tap_stride, kk_stride, lane, bq, acc);
     TRACE(3 + 4 * c);
-    if (more) activate((c + 1) * KC, s_a + ((c + 1) & 1) * BUF);
+    issue(mine, c + 2);
+    if (more) activate(next, (c + 1) * KC, s_a + ((c + 1) & 1) * BUF);
     TRACE(4 + 4 * c);
     __syncthreads();          // other buffer staged; this one free for chunk c+2
     TRACE(5 + 4 * c);
+  };
+
+  TRACE(0);
+  issue(raw0, 0);
+  issue(raw1, 1);
+  __syncthreads();            // scale/shift table complete
+  activate(raw0, 0, s_a);
+  __syncthreads();
+  TRACE(1);
+  for (int c = 0; c < nchunks; c += 2) {
+    chunk_step(c, raw0, raw1);
+    if (c + 1 < nchunks) chunk_step(c + 1, raw1, raw0);
   }
 
   // ---- epilogue: bias, residual, one rounding, store (through a wavefront-private LDS patch over the tile buffers)
@@ -431,7 +442,7 @@ bool conv_mfma_supported(const ConvArgs& a) {
   if (a.cout % 64 != 0 && !(a.y_nchw && a.cout <= 32)) return false;
   if (a.cin > 2048) return false;   // scale/shift table lives in LDS
   if (a.ksize != 1 && a.ksize != 3) return false;
-  if ((long)a.h * a.w * a.cin >= (1L << 31) || (long)a.h * a.w * a.cout >= (1L << 31)) return false;   // 32-bit pixel offsets
+  if ((long)a.h * a.w * a.cin >= (1L << 29) || (long)a.h * a.w * a.cout >= (1L << 29)) return false;   // 32-bit byte offsets per sample
   return true;
 }
 
