@@ -227,7 +227,7 @@ static int build_plan(wmdec_decoder& d) {
     Step f; f.kind = Step::FLASH; f.h = h; f.w = w; f.cin = c0;
     f.flops = 4.0 * (double)(h * w) * (double)(h * w) * c0;
     f.bytes = 4.0 * h * w * c0 * dtype_size(c.act_dtype);
-    d.steps.push_back(f); d.launches += 1;
+    d.steps.push_back(f); d.launches += 2;
     d.flops += f.flops;
     Step p; p.kind = Step::CONV; p.to_attn = 2; p.dst = other(1); p.res = cur; p.h = h; p.w = w; p.cin = c0; p.cout = c0; p.ksize = 1;
     B.conv_params("mid.attn.proj", c0, c0, 1, &p.w_off, &p.b_off);
@@ -279,7 +279,7 @@ static const Param* find_param(const wmdec_decoder* d, const char* name) {
 
 // layout of the workspace for `batch` frames
 struct WsLayout {
-  size_t act[3], qkv, vt, attn_o, mean, rstd, stats_ws, stats_ws_bytes, qkv_bias, total;
+  size_t act[3], qkv, vt, attn_o, attn_scratch, mean, rstd, stats_ws, stats_ws_bytes, total;
 };
 
 static WsLayout ws_layout(const wmdec_decoder* d, int batch) {
@@ -291,6 +291,7 @@ static WsLayout ws_layout(const wmdec_decoder* d, int batch) {
   L.qkv = o; o += align_up((size_t)batch * d->attn_t * 3 * d->attn_c * es, 256);
   L.vt = o; o += align_up((size_t)batch * d->attn_c * d->attn_tpad * es, 256);
   L.attn_o = o; o += align_up((size_t)batch * d->attn_t * d->attn_c * es, 256);
+  L.attn_scratch = o; o += align_up(flash_attention_scratch_bytes(batch, d->attn_t, d->attn_c), 256);
   L.mean = o; o += align_up((size_t)batch * d->cfg.groups * sizeof(float), 256);
   L.rstd = o; o += align_up((size_t)batch * d->cfg.groups * sizeof(float), 256);
   L.stats_ws_bytes = gn_stats_workspace_bytes(batch, 1, 1, 1, d->cfg.groups);
@@ -416,26 +417,27 @@ int wmdec_nhwc_to_nchw(const void* src, int sd, void* dst, int dd, int n, int c,
 }
 
 // ---- attention
-static void attn_ws_layout(int n, int t, int c, size_t es, size_t* qkv, size_t* vt, size_t* o, size_t* total) {
+static void attn_ws_layout(int n, int t, int c, size_t es, size_t* qkv, size_t* vt, size_t* o, size_t* scratch, size_t* total) {
   const int tpad = (t + 31) / 32 * 32;
   size_t off = 0;
   *qkv = off; off += align_up((size_t)n * t * 3 * c * es, 256);
   *vt = off; off += align_up((size_t)n * c * tpad * es, 256);
   *o = off; off += align_up((size_t)n * t * c * es, 256);
+  *scratch = off; off += align_up(flash_attention_scratch_bytes(n, t, c), 256);
   *total = off;
 }
 
 size_t wmdec_attention_workspace_bytes(int n, int h, int w, int c) {
   if (n <= 0 || h <= 0 || w <= 0 || c <= 0) return 0;
-  size_t a, b, d, total;
-  attn_ws_layout(n, h * w, c, 2, &a, &b, &d, &total);
+  size_t a, b, d, e, total;
+  attn_ws_layout(n, h * w, c, 2, &a, &b, &d, &e, &total);
   return total;
 }
 
 static int attention_impl(const void* x, int act_dtype, const float* mean, const float* rstd, const float* gamma,
                           const float* beta, int groups, const void* wqkv, const float* bqkv, const void* wo,
                           const float* bo, void* y, int n, int h, int w, int c, void* qkv, void* vt, void* ob,
-                          hipStream_t s) {
+                          void* scratch, hipStream_t s) {
   const int t = h * w, tpad = (t + 31) / 32 * 32;
   const size_t es = 2;
   ConvArgs a;
@@ -449,7 +451,7 @@ static int attention_impl(const void* x, int act_dtype, const float* mean, const
                         (size_t)t * 3 * c, (size_t)tpad, (size_t)c * tpad, s);
   if (rc != WMDEC_OK) return rc;
   rc = launch_flash_attention(qkv, (const char*)qkv + (size_t)c * es, (size_t)3 * c, (size_t)t * 3 * c, vt, tpad, ob,
-                              act_dtype, n, t, c, 1.0f / sqrtf((float)c), s);
+                              scratch, act_dtype, n, t, c, 1.0f / sqrtf((float)c), s);
   if (rc != WMDEC_OK) return rc;
   ConvArgs p;
   p.x = ob; p.x_dtype = act_dtype; p.wt = wo; p.op_dtype = act_dtype; p.bias = bo; p.res = x; p.res_dtype = act_dtype;
@@ -470,13 +472,13 @@ int wmdec_attention(const void* x, int act_dtype, const float* mean, const float
   WMDEC_REQUIRE(x != y, WMDEC_ERR_INVALID_ARG, "attention: x and y must not overlap");
   WMDEC_REQUIRE(aligned16(x) && aligned16(y) && aligned16(workspace) && aligned16(wqkv_packed) && aligned16(wo_packed),
                 WMDEC_ERR_INVALID_ARG, "attention: pointers must be 16-byte aligned");
-  size_t qo, vo, oo, total;
-  attn_ws_layout(n, h * w, c, 2, &qo, &vo, &oo, &total);
+  size_t qo, vo, oo, so, total;
+  attn_ws_layout(n, h * w, c, 2, &qo, &vo, &oo, &so, &total);
   WMDEC_REQUIRE(workspace && workspace_bytes >= total, WMDEC_ERR_WORKSPACE, "attention: workspace needs %zu bytes, got %zu",
                 total, workspace_bytes);
   char* ws = (char*)workspace;
   return attention_impl(x, act_dtype, mean, rstd, gamma, beta, groups, wqkv_packed, bqkv, wo_packed, bo, y, n, h, w, c,
-                        ws + qo, ws + vo, ws + oo, (hipStream_t)stream);
+                        ws + qo, ws + vo, ws + oo, ws + so, (hipStream_t)stream);
 }
 
 // ---- decoder
@@ -641,7 +643,7 @@ int decoder_run(wmdec_decoder* dec, const void* latent, const void* packed, void
         const size_t es = dtype_size(c.act_dtype);
         const int t = st.h * st.w;
         rc = launch_flash_attention(ws + L.qkv, ws + L.qkv + (size_t)st.cin * es, (size_t)3 * st.cin, (size_t)t * 3 * st.cin,
-                                    ws + L.vt, dec->attn_tpad, ws + L.attn_o, c.act_dtype, batch, t, st.cin,
+                                    ws + L.vt, dec->attn_tpad, ws + L.attn_o, ws + L.attn_scratch, c.act_dtype, batch, t, st.cin,
                                     1.0f / sqrtf((float)st.cin), s);
         break;
       }

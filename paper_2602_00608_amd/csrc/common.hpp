@@ -115,8 +115,10 @@ int launch_copy_f32(const float* src, float* dst, size_t count, hipStream_t s);
 
 // kernels_attn.hip
 // q,k: [n][t][ld] rows of d elements (16-bit type), vt: [n][d][t_pad] keys contiguous, o: [n][t][d]
+// scratch: flash_attention_scratch_bytes(n, t, d) bytes (partial outputs of the key splits), may be null if 0
+size_t flash_attention_scratch_bytes(int n, int t, int d);
 int launch_flash_attention(const void* q, const void* k, size_t qk_ld, size_t qk_batch_stride,
-                           const void* vt, int t_pad, void* o, int dtype, int n, int t, int d,
+                           const void* vt, int t_pad, void* o, void* scratch, int dtype, int n, int t, int d,
                            float scale, hipStream_t s);
 
 }  // namespace wmdec

@@ -7,6 +7,15 @@
 //   O^T[d][query]  += V^T * P^T    (A = V^T rows from LDS, B = P^T straight from the S^T registers)
 // In both, one lane owns one query column (n = lane % 16), so the softmax row
 // statistics are per lane plus a reduction over the 4 lanes that share a query.
+//
+// A workgroup of 8 wavefronts owns 128 queries (16 per wavefront) so that a K / V^T
+// tile staged in LDS serves all of them.  With d = 512 the output accumulator
+// (128 registers per lane) leaves room for only 16 queries per wavefront, which makes the
+// kernel LDS-bandwidth bound; to fill 256 compute units with only T/128 query blocks the
+// keys are split into `splits` ranges handled by different workgroups, each writing an
+// unnormalised partial output with its (max, sum); attn_combine merges them in a fixed order.
+// The next K tile is fetched into registers during the score phase and the next V^T
+// tile during the PV phase (two barriers per key block).
 #include "mfma.hpp"
 
 namespace wmdec {
@@ -15,25 +24,32 @@ namespace {
 constexpr int D = 512;            // head dimension
 constexpr int KB = 32;            // keys per block
 constexpr int QW = 16;            // queries per wavefront
-constexpr int WAVES = 4;
+constexpr int WAVES = 8;
+constexpr int NT = WAVES * 64;    // threads per workgroup
 constexpr int QB = QW * WAVES;    // queries per workgroup
 constexpr int K_LD = D + 8;       // LDS row stride of the K tile (elements): +16 B against bank conflicts
 constexpr int V_LD = KB + 4;      // LDS row stride of the V^T tile (elements)
+constexpr int KV = KB * (D / 8) / NT;   // 16-byte vectors of a tile per thread (= 4)
 
 template <typename T>
-__global__ __launch_bounds__(256) void flash_attn_kernel(const T* __restrict__ q, const T* __restrict__ k, size_t ld,
-                                                         size_t batch_stride, const T* __restrict__ vt, int t_pad,
-                                                         T* __restrict__ o, int t, float scale_log2e) {
+__global__ __launch_bounds__(NT) void flash_attn_kernel(const T* __restrict__ q, const T* __restrict__ k, size_t ld,
+                                                        size_t batch_stride, const T* __restrict__ vt, int t_pad,
+                                                        T* __restrict__ o, float* __restrict__ opart,
+                                                        float* __restrict__ ml, int t, int splits, float scale_log2e) {
   extern __shared__ __align__(16) unsigned char smem[];
   T* s_k = reinterpret_cast<T*>(smem);                 // [KB][K_LD]
   T* s_v = s_k + KB * K_LD;                            // [D][V_LD]
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int n = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = blockIdx.z, split = blockIdx.y;
   const int q0 = blockIdx.x * QB + wave * QW;
   const int lq = lane & 15, lg = lane >> 4;            // query column, lane group
   q += (size_t)n * batch_stride; k += (size_t)n * batch_stride;
-  vt += (size_t)n * D * t_pad; o += (size_t)n * t * D;
+  vt += (size_t)n * D * t_pad;
+  // key blocks of this split
+  const int nkb = (t + KB - 1) / KB;
+  const int kb_begin = (int)((long)split * nkb / splits) * KB, kb_end = (int)((long)(split + 1) * nkb / splits) * KB;
 
   // Q fragment: B[k = d][n = query] = Q[q0 + lq][32*step + 8*lg + j]
   u32x4 qf[D / 32];
@@ -43,40 +59,60 @@ __global__ __launch_bounds__(256) void flash_attn_kernel(const T* __restrict__ q
 #pragma unroll
     for (int st = 0; st < D / 32; ++st) qf[st] = src[st * 4 + lg];
   }
-
   f32x4 acc[D / 16];
 #pragma unroll
   for (int i = 0; i < D / 16; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
   float m_run = -INFINITY, l_run = 0.f;
 
-  for (int kb = 0; kb < t; kb += KB) {
-    __syncthreads();
-    // K tile: KB rows of D elements, 16 B per thread
-    for (int i = tid; i < KB * (D / 8); i += 256) {
-      const int r = i / (D / 8), c = i % (D / 8);
-      u32x4 v = u32x4{0u, 0u, 0u, 0u};
-      if (kb + r < t) v = reinterpret_cast<const u32x4*>(k + (size_t)(kb + r) * ld)[c];
-      *reinterpret_cast<u32x4*>(s_k + r * K_LD + c * 8) = v;
+  // staging: thread -> KV vectors of the K tile (row r, 16-byte column c) and of the V^T tile (row d, 8 keys)
+  u32x4 pre[KV];
+  auto load_k = [&](int kb) {
+#pragma unroll
+    for (int i = 0; i < KV; ++i) {
+      const int v = tid + i * NT, r = v / (D / 8), c = v % (D / 8);
+      pre[i] = reinterpret_cast<const u32x4*>(k + (size_t)min(kb + r, t - 1) * ld)[c];   // rows past t are masked later
     }
-    // V^T tile: D rows of KB keys; keys >= t are zeroed
-    for (int i = tid; i < D * (KB / 8); i += 256) {
-      const int r = i / (KB / 8), c = i % (KB / 8);
+  };
+  auto store_k = [&]() {
+#pragma unroll
+    for (int i = 0; i < KV; ++i) {
+      const int v = tid + i * NT, r = v / (D / 8), c = v % (D / 8);
+      *reinterpret_cast<u32x4*>(s_k + r * K_LD + c * 8) = pre[i];
+    }
+  };
+  auto load_v = [&](int kb) {
+#pragma unroll
+    for (int i = 0; i < KV; ++i) {
+      const int v = tid + i * NT, r = v / (KB / 8), c = v % (KB / 8);
+      pre[i] = reinterpret_cast<const u32x4*>(vt + (size_t)r * t_pad + min(kb, t_pad - KB) + c * 8)[0];
+    }
+  };
+  auto store_v = [&](int kb) {   // keys >= t are zeroed: their probability is 0 but 0 * garbage could be NaN
+#pragma unroll
+    for (int i = 0; i < KV; ++i) {
+      const int v = tid + i * NT, r = v / (KB / 8), c = v % (KB / 8);
       const int key = kb + c * 8;
-      u32x4 v = u32x4{0u, 0u, 0u, 0u};
-      if (key < t_pad) v = reinterpret_cast<const u32x4*>(vt + (size_t)r * t_pad + key)[0];
+      uint32_t w[4] = {pre[i].x, pre[i].y, pre[i].z, pre[i].w};
       if (key + 8 > t) {
-        uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int e = 0; e < 8; ++e)
           if (key + e >= t) w[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
-        v = u32x4{w[0], w[1], w[2], w[3]};
       }
       T* dst = s_v + r * V_LD + c * 8;
-      *reinterpret_cast<u32x2*>(dst) = u32x2{v.x, v.y};
-      *reinterpret_cast<u32x2*>(dst + 4) = u32x2{v.z, v.w};
+      *reinterpret_cast<u32x2*>(dst) = u32x2{w[0], w[1]};
+      *reinterpret_cast<u32x2*>(dst + 4) = u32x2{w[2], w[3]};
     }
-    __syncthreads();
+  };
 
+  if (kb_begin < kb_end) {
+    load_k(kb_begin); store_k();
+    load_v(kb_begin); store_v(kb_begin);
+  }
+  __syncthreads();
+
+  for (int kb = kb_begin; kb < kb_end; kb += KB) {
+    const int kn = min(kb + KB, kb_end - KB);   // next block (the last iteration reloads its own: harmless)
+    load_k(kn);
     // S^T tiles: keys kb + 16*tile + 4*lg + r, query q0 + lq
     f32x4 s0 = f32x4{0.f, 0.f, 0.f, 0.f}, s1 = s0;
 #pragma unroll
@@ -99,56 +135,116 @@ __global__ __launch_bounds__(256) void flash_attn_kernel(const T* __restrict__ q
     bm = fmaxf(bm, __shfl_xor(bm, 32));
     const float m_new = fmaxf(m_run, bm);   // finite: every block holds at least one valid key
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    float p[8], ps = 0.f;
+    float pr[8], ps = 0.f;
 #pragma unroll
-    for (int r = 0; r < 8; ++r) { p[r] = __builtin_amdgcn_exp2f(sv[r] - m_new); ps += p[r]; }
+    for (int r = 0; r < 8; ++r) { pr[r] = __builtin_amdgcn_exp2f(sv[r] - m_new); ps += pr[r]; }
     l_run = l_run * alpha + ps;
     m_run = m_new;
     // P^T fragment: contraction slots 8*lg + j  <->  keys {4*lg + j (tile 0), 16 + 4*lg + j - 4 (tile 1)}
-    const u32x4 pf = u32x4{pack2<T>(p[0], p[1]), pack2<T>(p[2], p[3]), pack2<T>(p[4], p[5]), pack2<T>(p[6], p[7])};
+    const u32x4 pf = u32x4{pack2<T>(pr[0], pr[1]), pack2<T>(pr[2], pr[3]), pack2<T>(pr[4], pr[5]), pack2<T>(pr[6], pr[7])};
+    __syncthreads();            // every wavefront is done with the K tile
+    store_k();                  // next K tile
+    load_v(kn);
+    const bool rescale = __any(alpha != 1.0f);
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt) {
       const T* row = s_v + (dt * 16 + lq) * V_LD;
       const u32x2 lo = *reinterpret_cast<const u32x2*>(row + 4 * lg);
       const u32x2 hi = *reinterpret_cast<const u32x2*>(row + 16 + 4 * lg);
       f32x4 c = acc[dt];
-      c *= alpha;
+      if (rescale) c *= alpha;
       acc[dt] = Mma<T>::m16(u32x4{lo.x, lo.y, hi.x, hi.y}, pf, c);
     }
+    __syncthreads();            // every wavefront is done with the V^T tile; next K tile visible
+    store_v(kn);
   }
 
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
-  const float inv = 1.0f / l_run;
   const int qr = q0 + lq;
-  if (qr < t) {
+  if (qr >= t) return;
+  if (splits == 1) {
+    const float inv = 1.0f / l_run;
+    T* orow = o + ((size_t)n * t + qr) * D;
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt) {
       const f32x4 c = acc[dt];
-      const u32x2 w = u32x2{pack2<T>(c[0] * inv, c[1] * inv), pack2<T>(c[2] * inv, c[3] * inv)};
-      *reinterpret_cast<u32x2*>(o + (size_t)qr * D + dt * 16 + 4 * lg) = w;
+      *reinterpret_cast<u32x2*>(orow + dt * 16 + 4 * lg) = u32x2{pack2<T>(c[0] * inv, c[1] * inv), pack2<T>(c[2] * inv, c[3] * inv)};
     }
+  } else {
+    const size_t row = ((size_t)n * splits + split) * t + qr;
+    float* prow = opart + row * D;
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) *reinterpret_cast<f32x4*>(prow + dt * 16 + 4 * lg) = acc[dt];
+    if (lg == 0) { ml[row * 2] = m_run; ml[row * 2 + 1] = l_run; }
   }
+}
+
+// o[n][q][:] = sum_s O_s 2^(m_s - M) / sum_s l_s 2^(m_s - M), splits merged in index order.
+// One workgroup of 128 threads per query, 4 consecutive d per thread.
+template <typename T>
+__global__ __launch_bounds__(128) void attn_combine_kernel(const float* __restrict__ opart, const float* __restrict__ ml,
+                                                           T* __restrict__ o, int t, int splits) {
+  const int qr = blockIdx.x, n = blockIdx.y, d0 = threadIdx.x * 4;
+  float mx = -INFINITY;
+  for (int s = 0; s < splits; ++s) mx = fmaxf(mx, ml[(((size_t)n * splits + s) * t + qr) * 2]);
+  float den = 0.f;
+  f32x4 num = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < splits; ++s) {
+    const size_t row = ((size_t)n * splits + s) * t + qr;
+    const float w = __builtin_amdgcn_exp2f(ml[row * 2] - mx);
+    den += w * ml[row * 2 + 1];
+    num += w * *reinterpret_cast<const f32x4*>(opart + row * D + d0);
+  }
+  const float inv = 1.0f / den;
+  *reinterpret_cast<u32x2*>(o + ((size_t)n * t + qr) * D + d0) =
+      u32x2{pack2<T>(num[0] * inv, num[1] * inv), pack2<T>(num[2] * inv, num[3] * inv)};
 }
 
 }  // namespace
 
+int flash_attention_splits(int n, int t) {
+  const int qblocks = (t + QB - 1) / QB, nkb = (t + KB - 1) / KB;
+  int s = (256 + n * qblocks - 1) / (n * qblocks);
+  if (s > 8) s = 8;
+  if (s > nkb) s = nkb;
+  return s < 1 ? 1 : s;
+}
+
+size_t flash_attention_scratch_bytes(int n, int t, int d) {
+  const int s = flash_attention_splits(n, t);
+  if (s == 1) return 0;
+  return (size_t)n * s * t * (d + 2) * sizeof(float);
+}
+
 int launch_flash_attention(const void* q, const void* k, size_t qk_ld, size_t qk_batch_stride, const void* vt,
-                           int t_pad, void* o, int dtype, int n, int t, int d, float scale, hipStream_t s) {
+                           int t_pad, void* o, void* scratch, int dtype, int n, int t, int d, float scale, hipStream_t s) {
   WMDEC_REQUIRE(d == D, WMDEC_ERR_UNSUPPORTED, "attention: head dimension %d is not supported (only %d)", d, D);
   WMDEC_REQUIRE(is_16bit(dtype), WMDEC_ERR_UNSUPPORTED, "attention: dtype must be BF16 or F16");
-  WMDEC_REQUIRE(t_pad % 8 == 0 && t_pad >= t && qk_ld % 8 == 0, WMDEC_ERR_SHAPE, "attention: bad leading dimensions");
+  WMDEC_REQUIRE(t_pad % KB == 0 && t_pad >= t && qk_ld % 8 == 0, WMDEC_ERR_SHAPE, "attention: bad leading dimensions");
+  const int splits = flash_attention_splits(n, t);
+  WMDEC_REQUIRE(splits == 1 || scratch, WMDEC_ERR_WORKSPACE, "attention: scratch for %d key splits missing", splits);
+  float* opart = (float*)scratch;
+  float* ml = opart ? opart + (size_t)n * splits * t * D : nullptr;
   const size_t smem = (size_t)(KB * K_LD + D * V_LD) * 2;
-  dim3 grid((unsigned)((t + QB - 1) / QB), (unsigned)n);
+  dim3 grid((unsigned)((t + QB - 1) / QB), (unsigned)splits, (unsigned)n);
   const float sl = scale * 1.4426950408889634f;
-  if (dtype == WMDEC_BF16) {
+  static bool attr_set = false;
+  if (!attr_set) {
     WMDEC_HIP(hipFuncSetAttribute((const void*)flash_attn_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    hipLaunchKernelGGL(flash_attn_kernel<bf16_t>, grid, dim3(256), smem, s, (const bf16_t*)q, (const bf16_t*)k, qk_ld,
-                       qk_batch_stride, (const bf16_t*)vt, t_pad, (bf16_t*)o, t, sl);
-  } else {
     WMDEC_HIP(hipFuncSetAttribute((const void*)flash_attn_kernel<f16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    hipLaunchKernelGGL(flash_attn_kernel<f16_t>, grid, dim3(256), smem, s, (const f16_t*)q, (const f16_t*)k, qk_ld,
-                       qk_batch_stride, (const f16_t*)vt, t_pad, (f16_t*)o, t, sl);
+    attr_set = true;
+  }
+  if (dtype == WMDEC_BF16) {
+    hipLaunchKernelGGL(flash_attn_kernel<bf16_t>, grid, dim3(NT), smem, s, (const bf16_t*)q, (const bf16_t*)k, qk_ld,
+                       qk_batch_stride, (const bf16_t*)vt, t_pad, (bf16_t*)o, opart, ml, t, splits, sl);
+    WMDEC_HIP(hipGetLastError());
+    if (splits > 1) hipLaunchKernelGGL(attn_combine_kernel<bf16_t>, dim3((unsigned)t, (unsigned)n), dim3(128), 0, s, opart, ml, (bf16_t*)o, t, splits);
+  } else {
+    hipLaunchKernelGGL(flash_attn_kernel<f16_t>, grid, dim3(NT), smem, s, (const f16_t*)q, (const f16_t*)k, qk_ld,
+                       qk_batch_stride, (const f16_t*)vt, t_pad, (f16_t*)o, opart, ml, t, splits, sl);
+    WMDEC_HIP(hipGetLastError());
+    if (splits > 1) hipLaunchKernelGGL(attn_combine_kernel<f16_t>, dim3((unsigned)t, (unsigned)n), dim3(128), 0, s, opart, ml, (f16_t*)o, t, splits);
   }
   WMDEC_HIP(hipGetLastError());
   return WMDEC_OK;
