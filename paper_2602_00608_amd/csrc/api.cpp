@@ -77,6 +77,8 @@ struct Step {
   int h = 0, w = 0, cin = 0, cout = 0;   // conv: OUTPUT h, w; stats: tensor h, w, c = cin
   int ksize = 3, upsample = 0, norm = 0, silu = 0;
   int x_nchw = 0, y_nchw = 0, to_attn = 0 /*1: dst is the qkv buffer, 2: src is the attention output*/;
+  int emit_stats = 0;      // CONV: its epilogue also writes the GroupNorm moments of its output
+  int from_producer = 0;   // STATS: only merge the moments the producing convolution left behind
   size_t w_off = 0, b_off = 0, gamma_off = 0, beta_off = 0;
   double flops = 0.0, bytes = 0.0;   // algorithmic work / HBM traffic of this step for one frame
 };
@@ -190,6 +192,38 @@ struct Builder {
   }
 };
 
+
+// the launch-shape part of a CONV step's arguments (pointers left null)
+static ConvArgs step_shape_args(const wmdec_decoder& d, const Step& st, int batch) {
+  ConvArgs a;
+  a.op_dtype = d.cfg.act_dtype; a.res_dtype = a.op_dtype;
+  a.x_dtype = st.src == BUF_LATENT ? (int)WMDEC_BF16 : a.op_dtype; a.x_nchw = st.x_nchw;
+  a.y_dtype = st.dst == BUF_OUT ? (int)WMDEC_F32 : a.op_dtype; a.y_nchw = st.y_nchw;
+  a.n = batch; a.h = st.h; a.w = st.w; a.cin = st.cin; a.cout = st.cout; a.ksize = st.ksize; a.upsample = st.upsample;
+  a.stats_groups = d.cfg.groups;
+  return a;
+}
+
+// Statistics passes whose input was written by a convolution that can emit moments in its epilogue become
+// a merge of those moments: the tensor is not read again.  One partial buffer exists, so a producer is used
+// only if no other emitting convolution runs between it and its statistics step.
+static void fuse_stats_into_producers(wmdec_decoder& d) {
+  for (size_t i = 0; i < d.steps.size(); ++i) {
+    Step& st = d.steps[i];
+    if (st.kind != Step::STATS || st.src < 0) continue;
+    int j = (int)i - 1;
+    while (j >= 0 && !(d.steps[j].kind == Step::CONV && d.steps[j].dst == st.src && d.steps[j].to_attn != 1)) --j;
+    if (j < 0) continue;
+    bool clash = false;
+    for (size_t k = j + 1; k < i; ++k) clash |= d.steps[k].kind == Step::CONV && d.steps[k].emit_stats;
+    if (clash || conv_mfma_stats_slots(step_shape_args(d, d.steps[j], 1)) <= 0) continue;
+    d.steps[j].emit_stats = 1;
+    st.from_producer = 1;
+    st.bytes = 0.0;          // no tensor traffic left in this step
+    d.launches -= 1;
+  }
+}
+
 static int build_plan(wmdec_decoder& d) {
   const wmdec_decoder_config& c = d.cfg;
   Builder B(d);
@@ -268,6 +302,7 @@ static int build_plan(wmdec_decoder& d) {
   }
   d.weights_bytes = B.off;
   d.packed_bytes = B.poff;
+  fuse_stats_into_producers(d);
   return WMDEC_OK;
 }
 
@@ -295,6 +330,11 @@ static WsLayout ws_layout(const wmdec_decoder* d, int batch) {
   L.mean = o; o += align_up((size_t)batch * d->cfg.groups * sizeof(float), 256);
   L.rstd = o; o += align_up((size_t)batch * d->cfg.groups * sizeof(float), 256);
   L.stats_ws_bytes = gn_stats_workspace_bytes(batch, 1, 1, 1, d->cfg.groups);
+  for (const Step& st : d->steps) {
+    if (st.kind != Step::CONV || !st.emit_stats) continue;
+    const size_t need = (size_t)batch * d->cfg.groups * conv_mfma_stats_slots(step_shape_args(*d, st, batch)) * 3 * sizeof(float);
+    if (need > L.stats_ws_bytes) L.stats_ws_bytes = need;
+  }
   L.stats_ws = o; o += align_up(L.stats_ws_bytes, 256);
   L.total = o;
   return L;
@@ -609,12 +649,16 @@ int decoder_run(wmdec_decoder* dec, const void* latent, const void* packed, void
   const bool prof = dec->profiling;
   if (prof) { dec->profiled_batch = batch; WMDEC_HIP(hipEventRecord(dec->events[0], s)); }
   size_t step_index = 0;
+  int emitted_slots = 0;   // moment slots per (sample, group) left by the last emitting convolution
   for (const Step& st : dec->steps) {
     int rc = WMDEC_OK;
     switch (st.kind) {
       case Step::STATS:
-        rc = launch_gn_stats(buf(st.src), c.act_dtype, batch, st.h, st.w, st.cin, c.groups, c.eps, mean, rstd,
-                             ws + L.stats_ws, L.stats_ws_bytes, s);
+        if (st.from_producer && emitted_slots > 0)
+          rc = launch_gn_finalize(ws + L.stats_ws, batch * c.groups, emitted_slots, c.eps, mean, rstd, s);
+        else
+          rc = launch_gn_stats(buf(st.src), c.act_dtype, batch, st.h, st.w, st.cin, c.groups, c.eps, mean, rstd,
+                               ws + L.stats_ws, L.stats_ws_bytes, s);
         break;
       case Step::CONV: {
         ConvArgs a;
@@ -629,6 +673,11 @@ int decoder_run(wmdec_decoder* dec, const void* latent, const void* packed, void
         else if (st.to_attn == 1) { a.y = ws + L.qkv; a.y_dtype = c.act_dtype; }
         else { a.y = buf(st.dst); a.y_dtype = c.act_dtype; }
         a.n = batch; a.h = st.h; a.w = st.w; a.cin = st.cin; a.cout = st.cout; a.ksize = st.ksize; a.upsample = st.upsample;
+        if (st.emit_stats) {
+          a.stats_groups = c.groups;
+          emitted_slots = conv_mfma_stats_slots(a);
+          if (emitted_slots > 0) a.stats_ws = ws + L.stats_ws;
+        }
         rc = launch_conv(a, s);
         break;
       }
@@ -678,7 +727,7 @@ int decoder_step_info(const wmdec_decoder* dec, int index, const char** kernel, 
   if (bytes) *bytes = st.bytes;
   if (kernel) {
     switch (st.kind) {
-      case Step::STATS: *kernel = "gn_stats"; break;
+      case Step::STATS: *kernel = st.from_producer ? "gn_finalize" : "gn_stats"; break;
       case Step::QKV_TRANSPOSE_V: *kernel = "transpose"; break;
       case Step::FLASH: *kernel = "flash_attn"; break;
       case Step::CONV: {

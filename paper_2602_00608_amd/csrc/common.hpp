@@ -87,6 +87,8 @@ struct ConvArgs {
   int cin = 0, cout = 0;
   int ksize = 3;                 // 1 or 3
   int upsample = 0;              // 1: input is [n,h/2,w/2,cin], gathered at (y>>1, x>>1)
+  void* stats_ws = nullptr;      // non-null: also emit GroupNorm moments of y, [n][stats_groups][slots] triples
+  int stats_groups = 0;
 };
 
 // kernels_conv_direct.hip: general VALU convolution (any shape, all dtypes).
@@ -95,6 +97,8 @@ int launch_conv_direct(const ConvArgs& a, hipStream_t s);
 // is not one it handles (caller falls back to the direct kernel), 0 if launched.
 bool conv_mfma_supported(const ConvArgs& a);
 int launch_conv_mfma(const ConvArgs& a, hipStream_t s);
+// moment slots per (sample, group) the MFMA kernel would write for this launch; 0: it cannot emit statistics
+int conv_mfma_stats_slots(const ConvArgs& a);
 // picks the kernel
 int launch_conv(const ConvArgs& a, hipStream_t s);
 const char* conv_kernel_label(const ConvArgs& a);
@@ -103,6 +107,9 @@ const char* conv_kernel_label(const ConvArgs& a);
 size_t gn_stats_workspace_bytes(int n, int h, int w, int c, int groups);
 int launch_gn_stats(const void* x, int x_dtype, int n, int h, int w, int c, int groups, float eps,
                     float* mean, float* rstd, void* ws, size_t ws_bytes, hipStream_t s);
+
+// merges `slots` moment triples per (sample, group) from ws[n_groups][slots] into mean / rstd
+int launch_gn_finalize(const void* ws, int n_groups, int slots, float eps, float* mean, float* rstd, hipStream_t s);
 
 // kernels_misc.hip
 int launch_upsample2x(const void* x, void* y, int dtype, int n, int h_in, int w_in, int c, hipStream_t s);

@@ -205,7 +205,8 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const float* __restri
 
 int flash_attention_splits(int n, int t) {
   const int qblocks = (t + QB - 1) / QB, nkb = (t + KB - 1) / KB;
-  int s = (256 + n * qblocks - 1) / (n * qblocks);
+  (void)n;   // independent of the batch, so that a frame's bits do not depend on what it is batched with
+  int s = (256 + qblocks - 1) / qblocks;
   if (s > 8) s = 8;
   if (s > nkb) s = nkb;
   return s < 1 ? 1 : s;

@@ -20,6 +20,7 @@
 #include <stdlib.h>
 
 #include "mfma.hpp"
+#include "moments.hpp"
 #include "pack_layout.hpp"
 
 namespace wmdec {
@@ -41,6 +42,8 @@ struct MfmaParams {
   int tiles_x, tiles_y, ntiles, total;
   int cin_blocks, cout_blocks;   // packed-layout extents: ceil(cin/16), ceil(cout/32)
   int y_nchw;                    // 1: y is planar [n][cout][h][w] (the frame), else NHWC
+  Moments* stats;                // non-null: moments of y per (sample, group, slot); slot = spatial tile * WM + wave row
+  int stats_cpg, stats_groups, stats_slots;
 #ifdef WMDEC_TRACE
   long long* trace;
 #endif
@@ -62,7 +65,7 @@ template <typename T> __device__ __forceinline__ void unpack8(const u32x4& v, fl
 template <typename T, typename TO, int MI, int NI, int MTW, int MTH, int MT_PER_ROW, bool RES>
 __device__ __forceinline__ void epilogue_store(const f32x16 (&acc)[MI][NI], float* lds, int lane, int mt0, int ty0,
                                                int tx0, int co_w, const float* bias, const T* rin, TO* yout, int h,
-                                               int w_out, int cout, bool nchw) {
+                                               int w_out, int cout, bool nchw, Moments* stats, int cpg, int stats_stride) {
   constexpr int RW = NI * 32 + 4;       // padded row of the patch, floats
   if (nchw) {
     // planar output with few channels (the frame): a lane owns one pixel of the M tile and walks the
@@ -109,6 +112,10 @@ __device__ __forceinline__ void epilogue_store(const f32x16 (&acc)[MI][NI], floa
 #pragma unroll
       for (int j = 0; j < VPL; ++j) rv[mi][j] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(rin) + (unsigned)(max(vec_off(mi, j), 0) * (int)sizeof(T)));
   }
+  // moments of the values this lane stores, per channel of its octet (shifted sums: the shift is the first value)
+  float st_shift[8], st_s[8], st_q[8], st_n = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { st_shift[e] = 0.f; st_s[e] = 0.f; st_q[e] = 0.f; }
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) {
 #pragma unroll
@@ -131,6 +138,15 @@ __device__ __forceinline__ void epilogue_store(const f32x16 (&acc)[MI][NI], floa
         if (mi + RD < MI)
           rv[mi % RD][j] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(rin) + (unsigned)(max(vec_off(mi + RD, j), 0) * (int)sizeof(T)));
       }
+      if (stats && off >= 0) {
+        if (st_n == 0.f) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) st_shift[e] = v[e];
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { const float dv = v[e] - st_shift[e]; st_s[e] += dv; st_q[e] = fmaf(dv, dv, st_q[e]); }
+        st_n += 1.f;
+      }
       if (off >= 0) {
         TO* dst = reinterpret_cast<TO*>(reinterpret_cast<char*>(yout) + (unsigned)(off * (int)sizeof(TO)));
         if constexpr (sizeof(TO) == 4) {
@@ -142,6 +158,35 @@ __device__ __forceinline__ void epilogue_store(const f32x16 (&acc)[MI][NI], floa
         }
       }
     }
+  }
+  if (stats) {
+    // lane -> wavefront: every lane parks its 8 channels' (count, shift, sum, sum of squares) in the LDS patch;
+    // lane L then owns channel L of the wavefront's run, re-centres the entries of the lanes that held that
+    // channel (they differ in the pixel rows they read back) on one shift and adds them in a fixed order.
+    constexpr int CV = NI * 4;                 // octets per row of the patch
+    constexpr int ROWS = 64 / CV;              // lanes per octet
+    f32x4* park = reinterpret_cast<f32x4*>(lds);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) park[lane * 8 + e] = f32x4{st_n, st_shift[e], st_s[e], st_q[e]};
+    Moments m{0.f, 0.f, 0.f};
+    if (lane < CV * 8) {
+      float n0 = 0.f, a0 = 0.f, s0 = 0.f, q0 = 0.f;
+#pragma unroll
+      for (int r = 0; r < ROWS; ++r) {
+        const f32x4 en = park[r * (CV * 8) + lane];     // (row r, octet lane / 8, channel lane % 8)
+        if (en[0] > 0.f) {
+          if (n0 == 0.f) a0 = en[1];
+          const float d = en[1] - a0;
+          s0 += en[2] + en[0] * d;
+          q0 += en[3] + 2.f * d * en[2] + en[0] * d * d;
+          n0 += en[0];
+        }
+      }
+      if (n0 > 0.f) { const float ds = s0 / n0; m.n = n0; m.mean = a0 + ds; m.m2 = fmaxf(q0 - s0 * ds, 0.f); }
+    }
+    // channels of one group are cpg consecutive lanes
+    for (int mask = 1; mask < cpg; mask <<= 1) m = butterfly(m, lane, mask);
+    if (lane < CV * 8 && (lane & (cpg - 1)) == 0) stats[(size_t)((co_w + lane) / cpg) * stats_stride] = m;
   }
 }
 
@@ -189,7 +234,7 @@ __device__ __forceinline__ void mfma_chunk(const T* buf, const int (&a_off)[MI],
 }
 
 template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC>
-__global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p) {
+__global__ __launch_bounds__(256, (TH * TW / 32 / WM) * NI <= 4 ? 3 : 2) void conv_mfma_kernel(MfmaParams p) {
   static_assert(WM * WN == 4, "four wavefronts");
   constexpr int MI = TH * TW / 32 / WM;          // 32-pixel M tiles per wavefront
   constexpr int PAD = KS / 2;
@@ -348,12 +393,14 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p) {
   TO* yout = reinterpret_cast<TO*>(p.y) + (size_t)n * p.h * p.w_out * p.cout;
   const T* rin = p.res ? reinterpret_cast<const T*>(p.res) + (size_t)n * p.h * p.w_out * p.cout : nullptr;
   float* patch = reinterpret_cast<float*>(smem) + wave * (32 * (NI * 32 + 4));
+  // statistics slot of this wavefront: [sample][group][spatial tile * WM + wave row]
+  Moments* st = p.stats ? p.stats + (size_t)n * p.stats_groups * p.stats_slots + (tile * WM + wm) : nullptr;
   if (rin)
     epilogue_store<T, TO, MI, NI, MTW, MTH, MT_PER_ROW, true>(acc, patch, lane, wm * MI, ty0, tx0, co0 + wn * NI * 32, p.bias,
-                                                              rin, yout, p.h, p.w_out, p.cout, false);
+                                                              rin, yout, p.h, p.w_out, p.cout, false, st, p.stats_cpg, p.stats_slots);
   else
     epilogue_store<T, TO, MI, NI, MTW, MTH, MT_PER_ROW, false>(acc, patch, lane, wm * MI, ty0, tx0, co0 + wn * NI * 32, p.bias,
-                                                               rin, yout, p.h, p.w_out, p.cout, p.y_nchw != 0);
+                                                               rin, yout, p.h, p.w_out, p.cout, p.y_nchw != 0, st, p.stats_cpg, p.stats_slots);
   TRACE(63);
 }
 
@@ -370,6 +417,8 @@ int launch_cfg(const ConvArgs& a, hipStream_t s) {
   p.tiles_x = (a.w + TW - 1) / TW; p.tiles_y = (a.h + TH - 1) / TH; p.ntiles = (a.cout + TN - 1) / TN;
   p.total = p.tiles_x * p.tiles_y * p.ntiles * a.n;
   p.cin_blocks = packed_cin_blocks(a.cin); p.cout_blocks = packed_cout_blocks(a.cout); p.y_nchw = a.y_nchw;
+  p.stats = (Moments*)a.stats_ws; p.stats_groups = a.stats_groups; p.stats_cpg = a.stats_groups > 0 ? a.cout / a.stats_groups : 1;
+  p.stats_slots = p.tiles_x * p.tiles_y * WM;
 #ifdef WMDEC_TRACE
   p.trace = g_trace;
 #endif
@@ -388,35 +437,56 @@ int launch_cfg(const ConvArgs& a, hipStream_t s) {
   return WMDEC_OK;
 }
 
+// Tile shapes: patch height x width, wavefront rows x columns, 32-channel tiles per wavefront.
+struct TileShape { int th, tw, wm, wn, ni; };
+constexpr TileShape kTiles[] = {
+    {8, 32, 2, 2, 2},    // 0: 256 pixels x 128 channels
+    {4, 32, 2, 2, 2},    // 1: 128 x 128, 4x32 patch
+    {4, 32, 4, 1, 2},    // 2: 128 x 64, 4x32 patch
+    {8, 32, 4, 1, 2},    // 3: 256 x 64
+    {8, 16, 2, 2, 2},    // 4: 128 x 128, 8x16 patch
+    {16, 16, 2, 2, 2},   // 5: 256 x 128, 16x16 patch
+    {8, 16, 4, 1, 2},    // 6: 128 x 64, 8x16 patch
+    {8, 32, 4, 1, 1},    // 7: 256 x 32 (few output channels: the frame)
+};
+
+// which tile shape a launch uses (3x3: any of the above; 1x1: 0, 1 or 2)
+int pick_tile(const ConvArgs& a) {
+  const long px = (long)a.h * a.w;   // per sample: the tiling, hence every summation order, does not depend on the batch
+  const bool n128 = a.cout % 128 == 0;
+  if (a.ksize == 3) {
+    if (a.cout <= 32) return 7;
+    int t = g_tile >= 0 && g_tile <= 6 ? g_tile : ((n128 && px * (a.cout / 128) >= 256L * 256 * 3) ? 0 : (n128 ? 4 : 6));
+    if (!n128 && (t == 0 || t == 1 || t == 4 || t == 5)) t = 6;
+    return t;
+  }
+  if (n128 && a.cin % 64 == 0 && px * (a.cout / 128) >= 256L * 256 * 2) return 0;
+  return n128 ? 1 : 2;
+}
+
 template <typename T, typename TO>
 int launch_3x3(const ConvArgs& a, hipStream_t s) {
-  const long px = (long)a.n * a.h * a.w;
-  if (a.cout <= 32) return launch_cfg<T, TO, 8, 32, 4, 1, 1, 3, 32>(a, s);   // few output channels (the frame): one 32-wide tile
-  const bool n128 = a.cout % 128 == 0;
-  int t = g_tile;
-  if (t < 0) t = (n128 && px * (a.cout / 128) >= 256L * 256 * 3) ? 0 : (n128 ? 4 : 6);
-  if (!n128 && (t == 0 || t == 1 || t == 4 || t == 5)) t = 6;
-  switch (t) {
-    case 0: return launch_cfg<T, TO, 8, 32, 2, 2, 2, 3, 32>(a, s);    // 256 pixels x 128 channels
-    case 1: return launch_cfg<T, TO, 4, 32, 2, 2, 2, 3, 32>(a, s);    // 128 x 128, 4x32 patch
-    case 2: return launch_cfg<T, TO, 4, 32, 4, 1, 2, 3, 32>(a, s);    // 128 x 64, 4x32 patch
-    case 3: return launch_cfg<T, TO, 8, 32, 4, 1, 2, 3, 32>(a, s);    // 256 x 64
-    case 4: return launch_cfg<T, TO, 8, 16, 2, 2, 2, 3, 32>(a, s);    // 128 x 128, 8x16 patch
-    case 5: return launch_cfg<T, TO, 16, 16, 2, 2, 2, 3, 32>(a, s);   // 256 x 128, 16x16 patch
-    default: return launch_cfg<T, TO, 8, 16, 4, 1, 2, 3, 32>(a, s);   // 128 x 64, 8x16 patch
+  switch (pick_tile(a)) {
+    case 0: return launch_cfg<T, TO, 8, 32, 2, 2, 2, 3, 32>(a, s);
+    case 1: return launch_cfg<T, TO, 4, 32, 2, 2, 2, 3, 32>(a, s);
+    case 2: return launch_cfg<T, TO, 4, 32, 4, 1, 2, 3, 32>(a, s);
+    case 3: return launch_cfg<T, TO, 8, 32, 4, 1, 2, 3, 32>(a, s);
+    case 4: return launch_cfg<T, TO, 8, 16, 2, 2, 2, 3, 32>(a, s);
+    case 5: return launch_cfg<T, TO, 16, 16, 2, 2, 2, 3, 32>(a, s);
+    case 6: return launch_cfg<T, TO, 8, 16, 4, 1, 2, 3, 32>(a, s);
+    default: return launch_cfg<T, TO, 8, 32, 4, 1, 1, 3, 32>(a, s);
   }
 }
 
 template <typename T, typename TO>
 int launch_1x1(const ConvArgs& a, hipStream_t s) {
-  const long px = (long)a.n * a.h * a.w;
-  const bool n128 = a.cout % 128 == 0;
-  if (a.cin % 64 == 0) {
-    if (n128 && px * (a.cout / 128) >= 256L * 256 * 2) return launch_cfg<T, TO, 8, 32, 2, 2, 2, 1, 64>(a, s);
-    if (n128) return launch_cfg<T, TO, 4, 32, 2, 2, 2, 1, 64>(a, s);
+  const int t = pick_tile(a);
+  if (a.cin % 64 == 0) {   // 64-channel chunks: half the barriers
+    if (t == 0) return launch_cfg<T, TO, 8, 32, 2, 2, 2, 1, 64>(a, s);
+    if (t == 1) return launch_cfg<T, TO, 4, 32, 2, 2, 2, 1, 64>(a, s);
     return launch_cfg<T, TO, 4, 32, 4, 1, 2, 1, 64>(a, s);
   }
-  if (n128) return launch_cfg<T, TO, 4, 32, 2, 2, 2, 1, 32>(a, s);
+  if (t == 1) return launch_cfg<T, TO, 4, 32, 2, 2, 2, 1, 32>(a, s);
   return launch_cfg<T, TO, 4, 32, 4, 1, 2, 1, 32>(a, s);
 }
 
@@ -446,9 +516,24 @@ bool conv_mfma_supported(const ConvArgs& a) {
   return true;
 }
 
-int launch_conv_mfma(const ConvArgs& a, hipStream_t s) {
+static void read_env_once() {
   static bool init = false;
   if (!init) { const char* t = getenv("WMDEC_CONV_TILE"); g_tile = t ? atoi(t) : -1; init = true; }
+}
+
+int conv_mfma_stats_slots(const ConvArgs& a) {
+  read_env_once();
+  if (!conv_mfma_supported(a) || a.y_nchw || a.stats_groups <= 0 || a.cout % a.stats_groups != 0) return 0;
+  const int cpg = a.cout / a.stats_groups;
+  if ((cpg & (cpg - 1)) != 0 || cpg > 32) return 0;   // a group must sit inside one wavefront's 64-channel run
+  int t = pick_tile(a);
+  if (a.ksize == 1 && a.cin % 64 != 0 && t == 0) t = 1;
+  const TileShape& ts = kTiles[t];
+  return ((a.w + ts.tw - 1) / ts.tw) * ((a.h + ts.th - 1) / ts.th) * ts.wm;
+}
+
+int launch_conv_mfma(const ConvArgs& a, hipStream_t s) {
+  read_env_once();
   return a.op_dtype == WMDEC_BF16 ? launch_type<bf16_t>(a, s) : launch_type<f16_t>(a, s);
 }
 

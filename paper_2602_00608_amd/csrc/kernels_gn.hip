@@ -8,31 +8,10 @@
 // writes one (count, mean, M2) triple per group.  Stage 2 (gn_finalize) merges
 // the triples of a group with the pairwise update of Chan et al. in a fixed
 // order, so the result does not depend on scheduling.
-#include "common.hpp"
+#include "moments.hpp"
 
 namespace wmdec {
 namespace {
-
-struct Moments { float n, mean, m2; };
-
-__device__ __forceinline__ Moments merge(Moments a, Moments b) {
-  if (b.n == 0.f) return a;
-  if (a.n == 0.f) return b;
-  const float n = a.n + b.n;
-  const float d = b.mean - a.mean;
-  const float fb = b.n / n;
-  Moments r;
-  r.n = n;
-  r.mean = a.mean + d * fb;
-  r.m2 = a.m2 + b.m2 + d * d * a.n * fb;
-  return r;
-}
-
-__device__ __forceinline__ Moments shfl_xor(Moments m, int mask) {
-  Moments r;
-  r.n = __shfl_xor(m.n, mask); r.mean = __shfl_xor(m.mean, mask); r.m2 = __shfl_xor(m.m2, mask);
-  return r;
-}
 
 template <typename T> struct Vec16;  // 16-byte vector of T
 template <> struct alignas(16) Vec16<float> { static constexpr int N = 4; float v[4]; };
@@ -162,11 +141,7 @@ __global__ __launch_bounds__(64) void gn_finalize(const Moments* __restrict__ ws
   const int ng = blockIdx.x, lane = threadIdx.x;
   Moments m{0.f, 0.f, 0.f};
   for (int i = lane; i < chunks; i += 64) m = merge(m, ws[(size_t)ng * chunks + i]);
-  for (int mask = 1; mask < 64; mask <<= 1) {
-    const Moments o = shfl_xor(m, mask);
-    // merge in a lane-independent order so that every lane ends with the same bits
-    m = (lane & mask) ? merge(o, m) : merge(m, o);
-  }
+  for (int mask = 1; mask < 64; mask <<= 1) m = butterfly(m, lane, mask);   // lane-independent order
   if (lane == 0) {
     mean[ng] = m.mean;
     rstd[ng] = 1.0f / sqrtf(m.m2 / m.n + eps);
@@ -204,6 +179,12 @@ Plan make_plan(int x_dtype, int n, int h, int w, int c, int groups) {
 }
 
 }  // namespace
+
+int launch_gn_finalize(const void* ws, int n_groups, int slots, float eps, float* mean, float* rstd, hipStream_t s) {
+  hipLaunchKernelGGL(gn_finalize, dim3((unsigned)n_groups), dim3(64), 0, s, (const Moments*)ws, slots, eps, mean, rstd);
+  WMDEC_HIP(hipGetLastError());
+  return WMDEC_OK;
+}
 
 size_t gn_stats_workspace_bytes(int n, int h, int w, int c, int groups) {
   // upper bound over dtypes: 2048 chunks per (sample, group)
