@@ -134,15 +134,19 @@ __global__ __launch_bounds__(256) void gn_partial_any(const T* __restrict__ x, i
   if (tid == 0) ws[((size_t)n * groups + g) * chunks + chunk] = s_m[0];
 }
 
-// grid = n*groups workgroups of 64 threads: lane l merges chunks l, l+64, ... in
-// order, then a fixed butterfly over the wavefront.
-__global__ __launch_bounds__(64) void gn_finalize(const Moments* __restrict__ ws, int chunks, float eps,
-                                                  float* __restrict__ mean, float* __restrict__ rstd) {
-  const int ng = blockIdx.x, lane = threadIdx.x;
+// grid = n*groups workgroups of 256 threads: thread t merges slots t, t+256, ... in order, then a fixed
+// butterfly over each wavefront, then wavefronts 0..3 in order.
+__global__ __launch_bounds__(256) void gn_finalize(const Moments* __restrict__ ws, int chunks, float eps,
+                                                   float* __restrict__ mean, float* __restrict__ rstd) {
+  __shared__ Moments s_w[4];
+  const int ng = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
   Moments m{0.f, 0.f, 0.f};
-  for (int i = lane; i < chunks; i += 64) m = merge(m, ws[(size_t)ng * chunks + i]);
+  for (int i = tid; i < chunks; i += 256) m = merge(m, ws[(size_t)ng * chunks + i]);
   for (int mask = 1; mask < 64; mask <<= 1) m = butterfly(m, lane, mask);   // lane-independent order
-  if (lane == 0) {
+  if (lane == 0) s_w[tid >> 6] = m;
+  __syncthreads();
+  if (tid == 0) {
+    m = merge(merge(s_w[0], s_w[1]), merge(s_w[2], s_w[3]));
     mean[ng] = m.mean;
     rstd[ng] = 1.0f / sqrtf(m.m2 / m.n + eps);
   }
@@ -181,7 +185,7 @@ Plan make_plan(int x_dtype, int n, int h, int w, int c, int groups) {
 }  // namespace
 
 int launch_gn_finalize(const void* ws, int n_groups, int slots, float eps, float* mean, float* rstd, hipStream_t s) {
-  hipLaunchKernelGGL(gn_finalize, dim3((unsigned)n_groups), dim3(64), 0, s, (const Moments*)ws, slots, eps, mean, rstd);
+  hipLaunchKernelGGL(gn_finalize, dim3((unsigned)n_groups), dim3(256), 0, s, (const Moments*)ws, slots, eps, mean, rstd);
   WMDEC_HIP(hipGetLastError());
   return WMDEC_OK;
 }
@@ -215,7 +219,7 @@ int launch_gn_stats(const void* x, int x_dtype, int n, int h, int w, int c, int 
     }
   }
   WMDEC_HIP(hipGetLastError());
-  hipLaunchKernelGGL(gn_finalize, dim3((unsigned)(n * groups)), dim3(64), 0, s, wsm, p.chunks, eps, mean, rstd);
+  hipLaunchKernelGGL(gn_finalize, dim3((unsigned)(n * groups)), dim3(256), 0, s, wsm, p.chunks, eps, mean, rstd);
   WMDEC_HIP(hipGetLastError());
   return WMDEC_OK;
 }

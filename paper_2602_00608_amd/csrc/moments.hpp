@@ -13,7 +13,7 @@ __device__ __forceinline__ Moments merge(Moments a, Moments b) {
   if (a.n == 0.f) return b;
   const float n = a.n + b.n;
   const float d = b.mean - a.mean;
-  const float fb = b.n / n;
+  const float fb = b.n * __builtin_amdgcn_rcpf(n);   // 1 ulp is ample for a weight
   Moments r;
   r.n = n;
   r.mean = a.mean + d * fb;
