@@ -19,6 +19,9 @@
 // other multiplies.
 #include <stdlib.h>
 
+#include <type_traits>
+#include <utility>
+
 #include "mfma.hpp"
 #include "moments.hpp"
 #include "pack_layout.hpp"
@@ -190,6 +193,12 @@ __device__ __forceinline__ void epilogue_store(const f32x16 (&acc)[MI][NI], floa
   }
 }
 
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>)
+template <int N, typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) { (f(std::integral_constant<int, I>{}), ...); }
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) { static_for_impl<N>(f, std::make_integer_sequence<int, N>{}); }
+
 // Ring length of the weight-fragment prefetch: it must divide the k-steps of a chunk so that the ring
 // position is the same at every chunk start.
 constexpr int prefetch_ring(int steps) { return steps % 3 == 0 ? 3 : (steps % 4 == 0 ? 4 : 2); }
@@ -201,39 +210,45 @@ constexpr int prefetch_ring(int steps) { return steps % 3 == 0 ? 3 : (steps % 4 
 // that consumed it, which gives the LDS read the rest of the step to land.  The scheduling
 // barriers pin that order: without them the compiler sinks every load to just before its use
 // and each k-step pays a full memory latency.
-template <typename T, int MI, int NI, int KS, int KC, int HW_, int PS, int D>
+template <typename T, int MI, int NI, int KS, int KC, int HW_, int PS, int D, bool SLICED, typename Slice>
 __device__ __forceinline__ void mfma_chunk(const T* buf, const int (&a_off)[MI], const u32x4* bcur, const u32x4* bnext,
                                            int tap_stride, int kk_stride, int lane, u32x4 (&bq)[D][NI],
-                                           f32x16 (&acc)[MI][NI]) {
+                                           f32x16 (&acc)[MI][NI], Slice&& slice) {
   constexpr int KK = KC / 16, STEPS = KS * KS * KK;
   u32x4 af[MI];
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) af[mi] = *reinterpret_cast<const u32x4*>(buf + a_off[mi]);
-#pragma unroll
-  for (int s = 0; s < STEPS; ++s) {
+  // one k-step; the slot hook runs after the MFMAs of every M tile so that its vector-ALU work issues
+  // while those MFMAs occupy the matrix pipe
+  auto step = [&](auto s_c) {
+    constexpr int s = decltype(s_c)::value;
     {
-      const int sp = s + D - 1;
+      constexpr int sp = s + D - 1;
       const u32x4* src = sp < STEPS ? bcur : bnext;
-      const int spp = sp < STEPS ? sp : sp - STEPS;
+      constexpr int spp = sp < STEPS ? sp : sp - STEPS;
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni)
         bq[sp % D][ni] = (src + ((spp / KK) * tap_stride + (spp % KK) * kk_stride + ni * 64))[lane];
     }
     __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi) {
+    auto tile = [&](auto mi_c) {
+      constexpr int mi = decltype(mi_c)::value;
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = Mma<T>::m32(af[mi], bq[s % D][ni], acc[mi][ni]);
-      if (s + 1 < STEPS) {
-        const int tap = (s + 1) / KK, kk = (s + 1) % KK;
+      if constexpr (s + 1 < STEPS) {
+        constexpr int tap = (s + 1) / KK, kk = (s + 1) % KK;
         af[mi] = *reinterpret_cast<const u32x4*>(buf + a_off[mi] + ((tap / KS) * HW_ + tap % KS) * PS + kk * 16);
       }
+      if constexpr (SLICED) slice(std::integral_constant<int, s * MI + mi>{});
       __builtin_amdgcn_sched_barrier(0);
-    }
-  }
+    };
+    static_for<MI>(tile);
+  };
+  static_for<STEPS>(step);
 }
 
-template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC>
+// ACT: what happens to an input element on its way into LDS: 0 nothing, 1 scale/shift, 2 scale/shift + SiLU
+template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC, int ACT>
 __global__ __launch_bounds__(256, (TH * TW / 32 / WM) * NI <= 4 ? 3 : 2) void conv_mfma_kernel(MfmaParams p) {
   static_assert(WM * WN == 4, "four wavefronts");
   constexpr int MI = TH * TW / 32 / WM;          // 32-pixel M tiles per wavefront
@@ -244,7 +259,9 @@ __global__ __launch_bounds__(256, (TH * TW / 32 / WM) * NI <= 4 ? 3 : 2) void co
   constexpr int TN = WN * NI * 32;
   constexpr int VPP = KC / 8;                    // 16-byte vectors per pixel per chunk
   constexpr int NV = (HP * VPP + 255) / 256;     // vectors a thread stages per chunk
-  constexpr int BUF = HP * PS;                   // elements of one staged tile
+  constexpr int BUF = (NV * 256 / VPP) * PS;     // elements of one staged tile (rounded up: every thread stores all its NV vectors)
+  constexpr int STEPS = KS * KS * (KC / 16), SLOTS = STEPS * MI;
+  constexpr bool SLICED = KS == 3;               // activation of the next chunk is sliced into the MFMA sweep
   static_assert(256 % VPP == 0, "a thread keeps one channel octet");
 
   extern __shared__ __align__(16) unsigned char smem[];
@@ -272,7 +289,7 @@ __global__ __launch_bounds__(256, (TH * TW / 32 / WM) * NI <= 4 ? 3 : 2) void co
   const int h_in = p.upsample ? p.h >> 1 : p.h, w_in = p.upsample ? p.w_out >> 1 : p.w_out;
 
   // per-channel scale/shift table: a = gamma*rstd, b = beta - mean*a
-  if (p.norm) {
+  if constexpr (ACT > 0) {
     const int cpg = p.cin / p.groups;
     for (int c = tid; c < p.cin; c += 256) {
       const int g = c / cpg;
@@ -324,69 +341,85 @@ __global__ __launch_bounds__(256, (TH * TW / 32 / WM) * NI <= 4 ? 3 : 2) void co
       src_off[i] = ((sy * w_in + sx) * p.cin + cvec * 8) * (int)sizeof(T);
     }
   }
-  // Two register sets of raw vectors: chunk k travels in set k & 1.  The loads of chunk k+2 are issued right
-  // after the MFMA sweep of chunk k, in front of the activation of chunk k+1: vector-memory loads return in
-  // order, so weight-fragment loads issued behind a batch of activation loads cannot be consumed before that
-  // batch has landed, and the activation phase is the one stretch in which no weight fragment is awaited.
-  u32x4 raw0[NV], raw1[NV];
-  // Unconditional loads (vectors outside the image read pixel 0 and are zeroed at activation): a load under
-  // a lane mask makes the compiler wait for it at the end of the branch.
-  auto issue = [&](u32x4 (&raw)[NV], int chunk) {
+  // One register set of raw vectors.  The loads of chunk k+1 are issued right after the MFMA sweep of chunk
+  // k-1 (vector-memory loads return in order, so weight-fragment loads issued behind them cannot be consumed
+  // before they have landed: the workgroup barrier and the first third of the next sweep cover that), and the
+  // vectors are activated and stored into the other LDS buffer in the last two thirds of the sweep of chunk k,
+  // a few elements after every M tile's MFMAs, so that this vector-ALU work overlaps the matrix pipe instead of
+  // forming a phase of its own.  Loads are unconditional (vectors outside the image read pixel 0 and are zeroed
+  // afterwards): a load under a lane mask makes the compiler wait for it at the end of the branch.
+  u32x4 raw[NV];
+  auto issue = [&](int chunk) {
     const int cb = min(chunk, p.cin / KC - 1) * KC * (int)sizeof(T);   // past the last chunk: a harmless reload
 #pragma unroll
     for (int i = 0; i < NV; ++i) raw[i] = *reinterpret_cast<const u32x4*>(xin + (unsigned)(max(src_off[i], 0) + cb));
   };
-  auto activate = [&](const u32x4 (&raw)[NV], int c0, T* buf) {   // scale/shift + SiLU + store into the staged tile
-    float sc[8], sh[8];
-    if (p.norm) {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) { const float2 ab = s_ab[c0 + cvec * 8 + j]; sc[j] = ab.x; sh[j] = ab.y; }
+  // word `part` (two channels) of vector i: scale/shift (+ SiLU) with the table entries of chunk channel c0
+  auto activate_word = [&](uint32_t wv, int i, int part, int c0) -> uint32_t {
+    if constexpr (ACT > 0) {
+      const f32x4 ab = *reinterpret_cast<const f32x4*>(s_ab + c0 + cvec * 8 + 2 * part);   // (a0, b0, a1, b1)
+      float f0 = fmaf(unpack_lo<T>(wv), ab[0], ab[1]), f1 = fmaf(unpack_hi<T>(wv), ab[2], ab[3]);
+      if constexpr (ACT == 2) { f0 = silu_f(f0); f1 = silu_f(f1); }
+      wv = pack2<T>(f0, f1);
     }
+    return src_off[i] >= 0 ? wv : 0u;   // zero padding acts on the activated tensor
+  };
+  auto store_vec = [&](int i, T* buf) {
+    *reinterpret_cast<u32x4*>(buf + ((tid + i * 256) / VPP) * PS + cvec * 8) = raw[i];
+  };
+  auto activate_all = [&](int c0, T* buf) {
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-      const int v = tid + i * 256;
-      if (v < HP * VPP) {
-        u32x4 out = src_off[i] >= 0 ? raw[i] : u32x4{0u, 0u, 0u, 0u};
-        if (p.norm && src_off[i] >= 0) {
-          float f[8];
-          unpack8<T>(out, f);
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            f[j] = fmaf(f[j], sc[j], sh[j]);
-            if (p.silu) f[j] = silu_f(f[j]);
-          }
-          out = u32x4{pack2<T>(f[0], f[1]), pack2<T>(f[2], f[3]), pack2<T>(f[4], f[5]), pack2<T>(f[6], f[7])};
-        }
-        *reinterpret_cast<u32x4*>(buf + (v / VPP) * PS + cvec * 8) = out;
-      }
+      raw[i] = u32x4{activate_word(raw[i].x, i, 0, c0), activate_word(raw[i].y, i, 1, c0),
+                     activate_word(raw[i].z, i, 2, c0), activate_word(raw[i].w, i, 3, c0)};
+      store_vec(i, buf);
     }
   };
   const int nchunks = p.cin / KC;
-  // one chunk: MFMA sweep of buffer c & 1, loads of chunk c+2 into the set just freed, activation of chunk c+1
-  auto chunk_step = [&](int c, u32x4 (&mine)[NV], const u32x4 (&next)[NV]) {
+
+  TRACE(0);
+  issue(0);
+  __syncthreads();            // scale/shift table complete
+  activate_all(0, s_a);
+  issue(1);
+  __syncthreads();
+  TRACE(1);
+  for (int c = 0; c < nchunks; ++c) {
     const bool more = c + 1 < nchunks;
     const u32x4* bcur = wcol + (size_t)(c * KK) * kk_stride;
     const u32x4* bnext = more ? bcur + (size_t)KK * kk_stride : bcur;
+    const T* buf = s_a + (c & 1) * BUF;
+    T* nbuf = s_a + ((c + 1) & 1) * BUF;
+    const int c0n = (c + 1) * KC;
     TRACE(2 + 4 * c);
-    mfma_chunk<T, MI, NI, KS, KC, HW_, PS, D>(s_a + (c & 1) * BUF, a_off, bcur, bnext, tap_stride, kk_stride, lane, bq, acc);
-    TRACE(3 + 4 * c);
-    issue(mine, c + 2);
-    if (more) activate(next, (c + 1) * KC, s_a + ((c + 1) & 1) * BUF);
+    if constexpr (SLICED) {
+      // slots FIRST .. SLOTS-1 share the NV*4 words of the next chunk evenly
+      auto slice = [&](auto slot_c) {
+        constexpr int slot = decltype(slot_c)::value;
+        constexpr int FIRST = SLOTS / 3, SPAN = SLOTS - FIRST, NW = NV * 4;
+        if constexpr (slot >= FIRST) {
+          constexpr int w0 = (slot - FIRST) * NW / SPAN, w1 = (slot - FIRST + 1) * NW / SPAN;
+          static_for<w1 - w0>([&](auto k_c) {
+            constexpr int wi = w0 + decltype(k_c)::value, i = wi / 4, part = wi % 4;
+            raw[i][part] = activate_word(raw[i][part], i, part, c0n);
+            if constexpr (part == 3) store_vec(i, nbuf);
+          });
+        }
+      };
+      // the last chunk activates a harmless reload into the buffer nobody reads: one instruction stream, no
+      // control flow inside the pinned schedule
+      mfma_chunk<T, MI, NI, KS, KC, HW_, PS, D, true>(buf, a_off, bcur, bnext, tap_stride, kk_stride, lane, bq, acc, slice);
+      TRACE(3 + 4 * c);
+    } else {
+      auto none = [](auto) {};
+      mfma_chunk<T, MI, NI, KS, KC, HW_, PS, D, false>(buf, a_off, bcur, bnext, tap_stride, kk_stride, lane, bq, acc, none);
+      TRACE(3 + 4 * c);
+      if (more) activate_all(c0n, nbuf);
+    }
+    issue(c + 2);
     TRACE(4 + 4 * c);
     __syncthreads();          // other buffer staged; this one free for chunk c+2
     TRACE(5 + 4 * c);
-  };
-
-  TRACE(0);
-  issue(raw0, 0);
-  issue(raw1, 1);
-  __syncthreads();            // scale/shift table complete
-  activate(raw0, 0, s_a);
-  __syncthreads();
-  TRACE(1);
-  for (int c = 0; c < nchunks; c += 2) {
-    chunk_step(c, raw0, raw1);
-    if (c + 1 < nchunks) chunk_step(c + 1, raw1, raw0);
   }
 
   // ---- epilogue: bias, residual, one rounding, store (through a wavefront-private LDS patch over the tile buffers)
@@ -422,15 +455,19 @@ int launch_cfg(const ConvArgs& a, hipStream_t s) {
 #ifdef WMDEC_TRACE
   p.trace = g_trace;
 #endif
-  size_t smem = (((size_t)2 * HP * (KC + 8) * 2 + 15) & ~(size_t)15) + (size_t)a.cin * sizeof(float2);
+  constexpr int NV = (HP * (KC / 8) + 255) / 256;
+  size_t smem = (((size_t)2 * (NV * 256 / (KC / 8)) * (KC + 8) * 2 + 15) & ~(size_t)15) + (size_t)a.cin * sizeof(float2);
   const size_t patch = (size_t)4 * 32 * (NI * 32 + 4) * sizeof(float);   // epilogue patches of the four wavefronts
   if (smem < patch) smem = patch;
   WMDEC_REQUIRE(smem <= 80 * 1024, WMDEC_ERR_UNSUPPORTED, "conv_mfma: %zu bytes of LDS needed", smem);
-  auto kern = conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC>;
-  static bool attr_set = false;   // per instantiation
-  if (!attr_set) {
+  void (*kern)(MfmaParams) = !p.norm ? conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 0>
+                             : (a.silu ? conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 2>
+                                       : conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 1>);
+  static bool attr_set[3] = {false, false, false};   // per instantiation and activation mode
+  const int mode = !p.norm ? 0 : (a.silu ? 2 : 1);
+  if (!attr_set[mode]) {
     WMDEC_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024));   // two workgroups per compute unit
-    attr_set = true;
+    attr_set[mode] = true;
   }
   hipLaunchKernelGGL(kern, dim3((unsigned)p.total), dim3(256), smem, s, p);
   WMDEC_HIP(hipGetLastError());
@@ -456,8 +493,8 @@ int pick_tile(const ConvArgs& a) {
   const bool n128 = a.cout % 128 == 0;
   if (a.ksize == 3) {
     if (a.cout <= 32) return 7;
-    int t = g_tile >= 0 && g_tile <= 6 ? g_tile : ((n128 && px * (a.cout / 128) >= 256L * 256 * 3) ? 0 : (n128 ? 4 : 6));
-    if (!n128 && (t == 0 || t == 1 || t == 4 || t == 5)) t = 6;
+    int t = (g_tile == 0 || g_tile == 4 || g_tile == 6) ? g_tile : ((n128 && px * (a.cout / 128) >= 256L * 256 * 3) ? 0 : (n128 ? 4 : 6));
+    if (!n128) t = 6;
     return t;
   }
   if (n128 && a.cin % 64 == 0 && px * (a.cout / 128) >= 256L * 256 * 2) return 0;
@@ -468,11 +505,7 @@ template <typename T, typename TO>
 int launch_3x3(const ConvArgs& a, hipStream_t s) {
   switch (pick_tile(a)) {
     case 0: return launch_cfg<T, TO, 8, 32, 2, 2, 2, 3, 32>(a, s);
-    case 1: return launch_cfg<T, TO, 4, 32, 2, 2, 2, 3, 32>(a, s);
-    case 2: return launch_cfg<T, TO, 4, 32, 4, 1, 2, 3, 32>(a, s);
-    case 3: return launch_cfg<T, TO, 8, 32, 4, 1, 2, 3, 32>(a, s);
     case 4: return launch_cfg<T, TO, 8, 16, 2, 2, 2, 3, 32>(a, s);
-    case 5: return launch_cfg<T, TO, 16, 16, 2, 2, 2, 3, 32>(a, s);
     case 6: return launch_cfg<T, TO, 8, 16, 4, 1, 2, 3, 32>(a, s);
     default: return launch_cfg<T, TO, 8, 32, 4, 1, 1, 3, 32>(a, s);
   }
