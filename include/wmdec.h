@@ -58,8 +58,13 @@ const char* wmdec_status_string(int status);
  *   group g of sample n = channels [g*c/groups, (g+1)*c/groups) over all h*w
  *   pixels;  mean[n*groups+g] = average,  rstd[...] = 1/sqrt(biased variance + eps).
  * x: [n,h,w,c] NHWC of x_dtype.  mean, rstd: fp32 [n*groups] outputs.
- * workspace: at least wmdec_gn_stats_workspace_bytes(...) bytes, contents
- * undefined before and after.  Errors: c % groups != 0 -> WMDEC_ERR_SHAPE. */
+ * workspace: at least wmdec_gn_stats_workspace_bytes(...) bytes of device
+ * memory, ZERO-FILLED once before the first call that uses it: its head holds
+ * one ticket counter per sample, which every call leaves at zero again, so
+ * the buffer can be reused (also with other shapes of the same n) without
+ * clearing.  The rest is scratch (contents undefined afterwards).
+ * Calls sharing a workspace must be ordered on one stream.
+ * Errors: c % groups != 0 -> WMDEC_ERR_SHAPE. */
 size_t wmdec_gn_stats_workspace_bytes(int n, int h, int w, int c, int groups);
 int wmdec_gn_stats(const void* x, int x_dtype, int n, int h, int w, int c, int groups, float eps,
                    float* mean, float* rstd, void* workspace, size_t workspace_bytes, void* stream);

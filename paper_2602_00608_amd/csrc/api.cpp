@@ -99,6 +99,7 @@ struct wmdec_decoder {
   int launches = 0;
   void* ws = nullptr;
   size_t ws_bytes = 0;
+  bool ws_fresh = true;    // the statistics ticket counter of a newly set workspace has not been zeroed yet
   bool profiling = false;
   int profiled_batch = 0;
   std::vector<hipEvent_t> events;   // steps.size() + 1 when profiling was ever enabled
@@ -314,7 +315,7 @@ static const Param* find_param(const wmdec_decoder* d, const char* name) {
 
 // layout of the workspace for `batch` frames
 struct WsLayout {
-  size_t act[3], qkv, vt, attn_o, attn_scratch, mean, rstd, stats_ws, stats_ws_bytes, total;
+  size_t tickets, act[3], qkv, vt, attn_o, attn_scratch, mean, rstd, stats_ws, stats_ws_bytes, total;
 };
 
 static WsLayout ws_layout(const wmdec_decoder* d, int batch) {
@@ -322,6 +323,7 @@ static WsLayout ws_layout(const wmdec_decoder* d, int batch) {
   const size_t es = dtype_size(d->cfg.act_dtype);
   const size_t act = align_up(d->act_elems_per_frame * es * batch, 256);
   size_t o = 0;
+  L.tickets = o; o += gn_stats_ticket_bytes(d->cfg.max_batch);   // same place and size for every batch: zeroed once
   for (int i = 0; i < 3; ++i) { L.act[i] = o; o += act; }
   L.qkv = o; o += align_up((size_t)batch * d->attn_t * 3 * d->attn_c * es, 256);
   L.vt = o; o += align_up((size_t)batch * d->attn_c * d->attn_tpad * es, 256);
@@ -329,7 +331,7 @@ static WsLayout ws_layout(const wmdec_decoder* d, int batch) {
   L.attn_scratch = o; o += align_up(flash_attention_scratch_bytes(batch, d->attn_t, d->attn_c), 256);
   L.mean = o; o += align_up((size_t)batch * d->cfg.groups * sizeof(float), 256);
   L.rstd = o; o += align_up((size_t)batch * d->cfg.groups * sizeof(float), 256);
-  L.stats_ws_bytes = gn_stats_workspace_bytes(batch, 1, 1, 1, d->cfg.groups);
+  L.stats_ws_bytes = gn_stats_moments_bytes(batch, d->cfg.groups);
   for (const Step& st : d->steps) {
     if (st.kind != Step::CONV || !st.emit_stats) continue;
     const size_t need = (size_t)batch * d->cfg.groups * conv_mfma_stats_slots(step_shape_args(*d, st, batch)) * 3 * sizeof(float);
@@ -361,7 +363,8 @@ const char* wmdec_status_string(int status) {
 
 size_t wmdec_gn_stats_workspace_bytes(int n, int h, int w, int c, int groups) {
   if (n <= 0 || h <= 0 || w <= 0 || c <= 0 || groups <= 0) return 0;
-  return gn_stats_workspace_bytes(n, h, w, c, groups);
+  (void)h; (void)w; (void)c;
+  return gn_stats_ticket_bytes(n) + gn_stats_moments_bytes(n, groups);
 }
 
 int wmdec_gn_stats(const void* x, int x_dtype, int n, int h, int w, int c, int groups, float eps, float* mean,
@@ -372,7 +375,10 @@ int wmdec_gn_stats(const void* x, int x_dtype, int n, int h, int w, int c, int g
   WMDEC_REQUIRE(c % groups == 0, WMDEC_ERR_SHAPE, "gn_stats: c %d not divisible by groups %d", c, groups);
   WMDEC_REQUIRE(eps >= 0.f, WMDEC_ERR_INVALID_ARG, "gn_stats: negative eps");
   WMDEC_REQUIRE(aligned16(x) && aligned16(workspace), WMDEC_ERR_INVALID_ARG, "gn_stats: pointers must be 16-byte aligned");
-  return launch_gn_stats(x, x_dtype, n, h, w, c, groups, eps, mean, rstd, workspace, workspace_bytes, (hipStream_t)stream);
+  const size_t head = gn_stats_ticket_bytes(n);
+  WMDEC_REQUIRE(workspace && workspace_bytes > head, WMDEC_ERR_WORKSPACE, "gn_stats: workspace of %zu bytes is too small", workspace_bytes);
+  return launch_gn_stats(x, x_dtype, n, h, w, c, groups, eps, mean, rstd, (unsigned*)workspace, (char*)workspace + head,
+                         workspace_bytes - head, (hipStream_t)stream);
 }
 
 size_t wmdec_conv_packed_bytes(int cout, int cin, int k, int op_dtype) {
@@ -630,6 +636,7 @@ int decoder_set_workspace(wmdec_decoder* dec, void* workspace, size_t bytes) {
   WMDEC_REQUIRE(aligned16(workspace), WMDEC_ERR_INVALID_ARG, "decoder_set_workspace: workspace must be 16-byte aligned");
   dec->ws = workspace;
   dec->ws_bytes = bytes;
+  dec->ws_fresh = true;
   return WMDEC_OK;
 }
 
@@ -646,6 +653,11 @@ int decoder_run(wmdec_decoder* dec, const void* latent, const void* packed, void
   float* mean = (float*)(ws + L.mean);
   float* rstd = (float*)(ws + L.rstd);
   auto buf = [&](int id) -> void* { return id >= 0 ? (void*)(ws + L.act[id]) : nullptr; };
+  if (dec->ws_fresh) {   // once per workspace: the ticket counter of the statistics kernel starts at zero
+    const int rc0 = launch_zero_u32(ws + L.tickets, (int)(gn_stats_ticket_bytes(dec->cfg.max_batch) / 4), s);
+    if (rc0 != WMDEC_OK) return rc0;
+    dec->ws_fresh = false;
+  }
   const bool prof = dec->profiling;
   if (prof) { dec->profiled_batch = batch; WMDEC_HIP(hipEventRecord(dec->events[0], s)); }
   size_t step_index = 0;
@@ -658,7 +670,7 @@ int decoder_run(wmdec_decoder* dec, const void* latent, const void* packed, void
           rc = launch_gn_finalize(ws + L.stats_ws, batch * c.groups, emitted_slots, c.eps, mean, rstd, s);
         else
           rc = launch_gn_stats(buf(st.src), c.act_dtype, batch, st.h, st.w, st.cin, c.groups, c.eps, mean, rstd,
-                               ws + L.stats_ws, L.stats_ws_bytes, s);
+                               (unsigned*)(ws + L.tickets), ws + L.stats_ws, L.stats_ws_bytes, s);
         break;
       case Step::CONV: {
         ConvArgs a;

@@ -104,9 +104,12 @@ int launch_conv(const ConvArgs& a, hipStream_t s);
 const char* conv_kernel_label(const ConvArgs& a);
 
 // kernels_gn.hip
-size_t gn_stats_workspace_bytes(int n, int h, int w, int c, int groups);
+// ticket: one zero-initialised counter per sample (gn_stats_ticket_bytes(n) bytes), left zero by every launch;
+// moments: scratch of at least gn_stats_moments_bytes(n, groups) bytes
+size_t gn_stats_ticket_bytes(int n);
+size_t gn_stats_moments_bytes(int n, int groups);
 int launch_gn_stats(const void* x, int x_dtype, int n, int h, int w, int c, int groups, float eps,
-                    float* mean, float* rstd, void* ws, size_t ws_bytes, hipStream_t s);
+                    float* mean, float* rstd, unsigned* ticket, void* moments, size_t moments_bytes, hipStream_t s);
 
 // merges `slots` moment triples per (sample, group) from ws[n_groups][slots] into mean / rstd
 int launch_gn_finalize(const void* ws, int n_groups, int slots, float eps, float* mean, float* rstd, hipStream_t s);
@@ -119,6 +122,7 @@ int launch_pack_conv(const void* src, int src_dtype, int cout, int cin, int k, v
 int launch_transpose(const void* src, int src_dtype, void* dst, int dst_dtype, int batch, int rows, int cols,
                      size_t src_ld, size_t src_batch_stride, size_t dst_ld, size_t dst_batch_stride, hipStream_t s);
 int launch_copy_f32(const float* src, float* dst, size_t count, hipStream_t s);
+int launch_zero_u32(void* p, int count, hipStream_t s);   // a fill kernel (safe under graph capture, unlike a memset node)
 
 // kernels_attn.hip
 // q,k: [n][t][ld] rows of d elements (16-bit type), vt: [n][d][t_pad] keys contiguous, o: [n][t][d]

@@ -13,93 +13,139 @@
 namespace wmdec {
 namespace {
 
+struct alignas(16) f32x4s { float x, y, z, w; };
+
 template <typename T> struct Vec16;  // 16-byte vector of T
 template <> struct alignas(16) Vec16<float> { static constexpr int N = 4; float v[4]; };
 template <> struct alignas(16) Vec16<bf16_t> { static constexpr int N = 8; bf16_t v[8]; };
 template <> struct alignas(16) Vec16<f16_t> { static constexpr int N = 8; f16_t v[8]; };
 
-// Fast path: c % V == 0, VP = c / V divides 256.  grid = (chunks, n).
-// ws: [n][groups][chunks] Moments.
+// Fast path: c % V == 0, vp = c / V divides 1024, channels per group a power of two <= 64.
+// grid = (chunks, n), 1024 threads.  ws: [n][groups][chunks] Moments.  One launch does everything: a workgroup
+// streams its slab (8 loads of 16 bytes in flight per thread, the ragged end as one masked batch), sums
+// x - shift and its square per thread (shift = the slab's first pixel, shared by all threads of a channel),
+// adds the threads of a channel in a fixed order through LDS, the channels of a group with a butterfly, and
+// writes one triple per group.  The workgroup of a sample that finishes last (one wrapping ticket counter per
+// sample, which returns to zero by itself) merges the sample's triples in a fixed order into mean / rstd.
+// device-scope (write-through / L2-bypassing) accesses of a triple, and the wait that orders them before a ticket
+__device__ __forceinline__ void store_device(Moments* p, Moments m) {
+  __hip_atomic_store(&p->n, m.n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(&p->mean, m.mean, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(&p->m2, m.m2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ Moments load_device(const Moments* p) {
+  Moments m;
+  m.n = __hip_atomic_load(&p->n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  m.mean = __hip_atomic_load(&p->mean, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  m.m2 = __hip_atomic_load(&p->m2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return m;
+}
+__device__ __forceinline__ void wait_stores() {
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): every store of this wavefront has been acknowledged
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+constexpr int kVecThreads = 1024;
+constexpr int kVecMaxChunks = 256;
+
+template <typename T, int V, bool MASKED>
+__device__ __forceinline__ void gn_accumulate(const Vec16<T>* base, int p, int p1, int ppi, int vp, const float* shift,
+                                              float* s, float* q) {
+  constexpr int U = 8;
+  Vec16<T> v[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int pp = p + u * ppi;
+    v[u] = base[(size_t)((MASKED && pp >= p1) ? p : pp) * vp];   // always a pixel of this slab: no branch around the load
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const bool live = !MASKED || p + u * ppi < p1;
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+      const float d = live ? to_float(v[u].v[j]) - shift[j] : 0.f;
+      s[j] += d;
+      q[j] = fmaf(d, d, q[j]);
+    }
+  }
+}
+
 template <typename T>
-__global__ __launch_bounds__(256) void gn_partial_vec(const T* __restrict__ x, int pixels, int c, int groups,
-                                                      int chunk_pixels, Moments* __restrict__ ws) {
+__global__ __launch_bounds__(kVecThreads) void gn_stats_vec(const T* __restrict__ x, int pixels, int c, int groups,
+                                                            int chunk_pixels, Moments* ws, unsigned* ticket, float eps,
+                                                            float* __restrict__ mean, float* __restrict__ rstd) {
   constexpr int V = Vec16<T>::N;
-  __shared__ Moments s_m[256];
+  constexpr int U = 8;
+  __shared__ float2 s_e[kVecThreads * V];   // (sum, sum of squares) per (pixel lane, channel)
+  __shared__ Moments s_g[kVecThreads];      // the slab's moments per group
+  __shared__ unsigned s_last;
   const int tid = threadIdx.x;
   const int vp = c / V;           // vectors per pixel
   const int cv = tid % vp;        // this thread's channel vector
-  const int ppi = 256 / vp;       // pixels per sweep of the workgroup
+  const int ppi = kVecThreads / vp;   // pixels per sweep of the workgroup
   const int chunk = blockIdx.x, n = blockIdx.y, chunks = gridDim.x;
   const int p0 = chunk * chunk_pixels;
   const int p1 = min(p0 + chunk_pixels, pixels);
   const Vec16<T>* base = reinterpret_cast<const Vec16<T>*>(x + (size_t)n * pixels * c) + cv;
 
   float shift[V], s[V], q[V];
-  float cnt = 0.f;
-  int p = p0 + tid / vp;
-  if (p < p1) {
-    const Vec16<T> v = base[(size_t)p * vp];
+  {
+    const Vec16<T> v = base[(size_t)p0 * vp];
 #pragma unroll
     for (int j = 0; j < V; ++j) { shift[j] = to_float(v.v[j]); s[j] = 0.f; q[j] = 0.f; }
-    cnt = 1.f;
-    p += ppi;
-  } else {
-#pragma unroll
-    for (int j = 0; j < V; ++j) { shift[j] = 0.f; s[j] = 0.f; q[j] = 0.f; }
   }
-  // four loads in flight per thread
-  for (; p + 3 * ppi < p1; p += 4 * ppi) {
-    Vec16<T> v[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) v[u] = base[(size_t)(p + u * ppi) * vp];
-#pragma unroll
-    for (int u = 0; u < 4; ++u)
-#pragma unroll
-      for (int j = 0; j < V; ++j) { const float d = to_float(v[u].v[j]) - shift[j]; s[j] += d; q[j] = fmaf(d, d, q[j]); }
-    cnt += 4.f;
-  }
-  for (; p < p1; p += ppi) {
-    const Vec16<T> v = base[(size_t)p * vp];
-#pragma unroll
-    for (int j = 0; j < V; ++j) { const float d = to_float(v.v[j]) - shift[j]; s[j] += d; q[j] = fmaf(d, d, q[j]); }
-    cnt += 1.f;
-  }
+  int p = p0 + tid / vp;
+  for (; p + (U - 1) * ppi < p1; p += U * ppi) gn_accumulate<T, V, false>(base, p, p1, ppi, vp, shift, s, q);
+  if (p < p1) gn_accumulate<T, V, true>(base, p, p1, ppi, vp, shift, s, q);
 
-  // per-thread moments of its V channels, merged per group.  A vector of V
-  // channels covers V/cpg groups when cpg < V, else lies inside one group.
-  const int cpg = c / groups;
-  const int sub = (cpg < V) ? cpg : V;   // channels of one group inside this vector
-  const int nsub = V / sub;              // groups touched by this vector (1, 2 or 4 ...)
-  // Reduce one sub-vector at a time through LDS: all threads of the workgroup
-  // that hold channels of the same group are merged in a fixed tree.
-  for (int sv = 0; sv < nsub; ++sv) {
-    Moments m{0.f, 0.f, 0.f};
-    if (cnt > 0.f) {
 #pragma unroll
-      for (int j = 0; j < V; ++j) {
-        if (j / sub == sv) {
-          Moments e;
-          e.n = cnt;
-          const float ds = s[j] / cnt;
-          e.mean = shift[j] + ds;
-          e.m2 = fmaxf(q[j] - s[j] * ds, 0.f);
-          m = merge(m, e);
-        }
-      }
+  for (int j = 0; j < V; ++j) s_e[(tid / vp) * c + cv * V + j] = float2{s[j], q[j]};
+  __syncthreads();
+  const int cpg = c / groups;
+  const float cnt = (float)(p1 - p0);
+  for (int ch = tid; ch < c; ch += kVecThreads) {
+    float s0 = 0.f, q0 = 0.f;
+#pragma unroll 8
+    for (int r = 0; r < ppi; ++r) { const float2 e = s_e[r * c + ch]; s0 += e.x; q0 += e.y; }
+    // every thread of a channel used the same shift: the slab's first pixel
+    const float a0 = to_float(x[((size_t)n * pixels + p0) * c + ch]);
+    const float ds = s0 / cnt;
+    Moments m{cnt, a0 + ds, fmaxf(q0 - s0 * ds, 0.f)};
+    for (int mask = 1; mask < cpg; mask <<= 1) m = butterfly(m, tid, mask);   // cpg consecutive lanes = one group
+    if ((ch & (cpg - 1)) == 0) s_g[ch / cpg] = m;
+  }
+  __syncthreads();
+
+  // One wavefront publishes the slab's triples and takes the sample's ticket.  No fences (a fence walks the whole
+  // L2 and costs microseconds per workgroup): the triples are written with device-scope stores, which go through
+  // to memory, the wavefront waits for them to complete before it takes the ticket, and the sample's last
+  // workgroup reads all triples with device-scope loads, which do not hit stale lines of its own L2.
+  if (tid < 64) {
+    for (int g = tid; g < groups; g += 64) store_device(ws + ((size_t)n * groups + g) * chunks + chunk, s_g[g]);
+    wait_stores();
+    if (tid == 0) s_last = atomicInc(ticket + n, chunks - 1) == (unsigned)(chunks - 1);
+  }
+  __syncthreads();
+  if (!s_last) return;
+  // half a wavefront per group, 8 slots per lane, merged in a fixed order
+  const int sub = tid & 31, half = tid >> 5;
+  for (int g = half; g < groups; g += kVecThreads / 32) {
+    const Moments* row = ws + ((size_t)n * groups + g) * chunks;
+    Moments t[kVecMaxChunks / 32];
+#pragma unroll
+    for (int k = 0; k < kVecMaxChunks / 32; ++k) {
+      const int i = sub + 32 * k;
+      t[k] = load_device(row + min(i, chunks - 1));
+      if (i >= chunks) t[k].n = 0.f;
     }
-    __syncthreads();
-    s_m[tid] = m;
-    __syncthreads();
-    // group of this thread's sub-vector: g = (cv*V + sv*sub) / cpg.  Threads with equal g:
-    // vectors_per_group = max(cpg / V, 1) consecutive cv values, times ppi pixel lanes.
-    const int vpg = (cpg >= V) ? cpg / V : 1;
-    const int g = (cv * V + sv * sub) / cpg;
-    // one leader thread per group does a fixed-order merge of its ppi*vpg members
-    if (tid / vp == 0 && (cv % vpg) == 0) {
-      Moments r{0.f, 0.f, 0.f};
-      for (int pl = 0; pl < ppi; ++pl)
-        for (int k = 0; k < vpg; ++k) r = merge(r, s_m[pl * vp + cv + k]);
-      ws[((size_t)n * groups + g) * chunks + chunk] = r;
+    Moments m = t[0];
+#pragma unroll
+    for (int k = 1; k < kVecMaxChunks / 32; ++k) m = merge(m, t[k]);
+    for (int mask = 1; mask < 32; mask <<= 1) m = butterfly(m, sub, mask);
+    if (sub == 0) {
+      mean[n * groups + g] = m.mean;
+      rstd[n * groups + g] = 1.0f / sqrtf(m.m2 / m.n + eps);
     }
   }
 }
@@ -134,14 +180,25 @@ __global__ __launch_bounds__(256) void gn_partial_any(const T* __restrict__ x, i
   if (tid == 0) ws[((size_t)n * groups + g) * chunks + chunk] = s_m[0];
 }
 
-// grid = n*groups workgroups of 256 threads: thread t merges slots t, t+256, ... in order, then a fixed
-// butterfly over each wavefront, then wavefronts 0..3 in order.
+// grid = n*groups workgroups of 256 threads: thread t merges slots t, t+256, ... in order (loaded eight at a time,
+// so that a row costs one memory round trip), then a fixed butterfly over each wavefront, then wavefronts 0..3 in order.
 __global__ __launch_bounds__(256) void gn_finalize(const Moments* __restrict__ ws, int chunks, float eps,
                                                    float* __restrict__ mean, float* __restrict__ rstd) {
   __shared__ Moments s_w[4];
   const int ng = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+  const Moments* row = ws + (size_t)ng * chunks;
   Moments m{0.f, 0.f, 0.f};
-  for (int i = tid; i < chunks; i += 256) m = merge(m, ws[(size_t)ng * chunks + i]);
+  for (int i0 = tid; i0 < chunks; i0 += 256 * 8) {
+    Moments t[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int i = i0 + 256 * k;
+      t[k] = row[min(i, chunks - 1)];
+      if (i >= chunks) t[k].n = 0.f;
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) m = merge(m, t[k]);
+  }
   for (int mask = 1; mask < 64; mask <<= 1) m = butterfly(m, lane, mask);   // lane-independent order
   if (lane == 0) s_w[tid >> 6] = m;
   __syncthreads();
@@ -153,11 +210,14 @@ __global__ __launch_bounds__(256) void gn_finalize(const Moments* __restrict__ w
 }
 
 int pick_chunks(int pixels, int c, int V, bool vec) {
-  // aim at <= 2048 workgroups per sample, each sweeping its slab at least 8 times
-  const int ppi = vec ? 256 / (c / V) : 1;
-  const int min_chunk = vec ? 8 * ppi : 1024;
+  // vector path: <= 256 workgroups of 1024 threads per sample (one per compute unit, 128 KiB of loads in flight),
+  // every one sweeping its slab at least 4 times; general path: <= 2048 slabs of >= 1024 pixels.
+  // Never a function of the batch size: a sample's result must not depend on its neighbours.
+  const int ppi = vec ? kVecThreads / (c / V) : 1;
+  const int min_chunk = vec ? 4 * ppi : 1024;
   int chunks = (pixels + min_chunk - 1) / min_chunk;
-  if (chunks > 2048) chunks = 2048;
+  const int cap = vec ? kVecMaxChunks : 2048;
+  if (chunks > cap) chunks = cap;
   if (chunks < 1) chunks = 1;
   return chunks;
 }
@@ -165,17 +225,17 @@ int pick_chunks(int pixels, int c, int V, bool vec) {
 struct Plan { bool vec; int chunks; int chunk_pixels; };
 
 Plan make_plan(int x_dtype, int n, int h, int w, int c, int groups) {
+  (void)n;
   const int V = x_dtype == WMDEC_F32 ? 4 : 8;
   const int pixels = h * w;
   const int cpg = c / groups;
   Plan p;
-  const bool divisible = (c % V == 0) && (256 % (c / V) == 0) && (c / V <= 256);
-  // a vector must not straddle a group boundary unevenly: cpg | V or V | cpg
-  p.vec = divisible && ((cpg % V == 0) || (V % cpg == 0));
+  const bool divisible = (c % V == 0) && (kVecThreads % (c / V) == 0) && c <= kVecThreads;
+  p.vec = divisible && (cpg & (cpg - 1)) == 0 && cpg <= 64;   // groups are runs of 2^k lanes in the channel reduction
   p.chunks = pick_chunks(pixels, c, V, p.vec);
   p.chunk_pixels = (pixels + p.chunks - 1) / p.chunks;
   if (p.vec) {
-    const int ppi = 256 / (c / V);
+    const int ppi = kVecThreads / (c / V);
     p.chunk_pixels = ((p.chunk_pixels + ppi - 1) / ppi) * ppi;
   }
   p.chunks = (pixels + p.chunk_pixels - 1) / p.chunk_pixels;
@@ -190,26 +250,30 @@ int launch_gn_finalize(const void* ws, int n_groups, int slots, float eps, float
   return WMDEC_OK;
 }
 
-size_t gn_stats_workspace_bytes(int n, int h, int w, int c, int groups) {
-  // upper bound over dtypes: 2048 chunks per (sample, group)
-  (void)h; (void)w; (void)c;
+// one ticket counter per sample for the single-launch path
+size_t gn_stats_ticket_bytes(int n) { return ((size_t)n * sizeof(unsigned) + 255) / 256 * 256; }
+
+size_t gn_stats_moments_bytes(int n, int groups) {
+  // upper bound over shapes and dtypes: 2048 chunks per (sample, group)
   return (size_t)n * groups * 2048 * sizeof(Moments);
 }
 
 int launch_gn_stats(const void* x, int x_dtype, int n, int h, int w, int c, int groups, float eps,
-                    float* mean, float* rstd, void* ws, size_t ws_bytes, hipStream_t s) {
+                    float* mean, float* rstd, unsigned* ticket, void* moments, size_t moments_bytes, hipStream_t s) {
   const Plan p = make_plan(x_dtype, n, h, w, c, groups);
-  WMDEC_REQUIRE(ws && ws_bytes >= (size_t)n * groups * p.chunks * sizeof(Moments), WMDEC_ERR_WORKSPACE,
-                "gn_stats: workspace of %zu bytes is too small", ws_bytes);
-  Moments* wsm = (Moments*)ws;
+  WMDEC_REQUIRE(ticket && moments && moments_bytes >= (size_t)n * groups * p.chunks * sizeof(Moments), WMDEC_ERR_WORKSPACE,
+                "gn_stats: workspace of %zu bytes is too small", moments_bytes);
+  Moments* wsm = (Moments*)moments;
   const int pixels = h * w;
   if (p.vec) {
     dim3 grid((unsigned)p.chunks, (unsigned)n);
     switch (x_dtype) {
-      case WMDEC_F32: hipLaunchKernelGGL(gn_partial_vec<float>, grid, dim3(256), 0, s, (const float*)x, pixels, c, groups, p.chunk_pixels, wsm); break;
-      case WMDEC_BF16: hipLaunchKernelGGL(gn_partial_vec<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)x, pixels, c, groups, p.chunk_pixels, wsm); break;
-      default: hipLaunchKernelGGL(gn_partial_vec<f16_t>, grid, dim3(256), 0, s, (const f16_t*)x, pixels, c, groups, p.chunk_pixels, wsm); break;
+      case WMDEC_F32: hipLaunchKernelGGL(gn_stats_vec<float>, grid, dim3(kVecThreads), 0, s, (const float*)x, pixels, c, groups, p.chunk_pixels, wsm, ticket, eps, mean, rstd); break;
+      case WMDEC_BF16: hipLaunchKernelGGL(gn_stats_vec<bf16_t>, grid, dim3(kVecThreads), 0, s, (const bf16_t*)x, pixels, c, groups, p.chunk_pixels, wsm, ticket, eps, mean, rstd); break;
+      default: hipLaunchKernelGGL(gn_stats_vec<f16_t>, grid, dim3(kVecThreads), 0, s, (const f16_t*)x, pixels, c, groups, p.chunk_pixels, wsm, ticket, eps, mean, rstd); break;
     }
+    WMDEC_HIP(hipGetLastError());
+    return WMDEC_OK;
   } else {
     dim3 grid((unsigned)p.chunks, (unsigned)groups, (unsigned)n);
     switch (x_dtype) {

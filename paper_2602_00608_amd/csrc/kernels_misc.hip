@@ -8,17 +8,23 @@ namespace {
 
 struct alignas(16) Chunk16 { uint32_t w[4]; };
 
-// y[n,oy,ox,:] = x[n,oy>>1,ox>>1,:]; one 16-byte chunk per thread (c*esize % 16 == 0)
+// y[n,oy,ox,:] = x[n,oy>>1,ox>>1,:] in 16-byte chunks (c*esize % 16 == 0): a thread reads one input chunk and
+// writes it to the four output pixels it maps to, so the input is read exactly once and the index arithmetic is
+// paid once per four stores.  A run of lanes covers whole pixels, i.e. every store instruction writes runs of
+// cpp*16 contiguous bytes.
 __global__ __launch_bounds__(256) void upsample2x_vec(const Chunk16* __restrict__ x, Chunk16* __restrict__ y,
-                                                      int h_in, int w_in, int cpp /*chunks per pixel*/, size_t total) {
-  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= total) return;
-  const int cc = (int)(i % cpp);
-  size_t pix = i / cpp;
-  const int ox = (int)(pix % (2 * w_in)); pix /= (2 * w_in);
-  const int oy = (int)(pix % (2 * h_in));
-  const size_t n = pix / (2 * h_in);
-  y[i] = x[((n * h_in + (oy >> 1)) * w_in + (ox >> 1)) * cpp + cc];
+                                                      int h_in, int w_in, int cpp /*chunks per pixel*/, size_t total_in) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total_in; i += (size_t)gridDim.x * 256) {
+    const Chunk16 v = x[i];
+    const int cc = (int)(i % cpp);
+    size_t pix = i / cpp;
+    const int ix = (int)(pix % w_in); pix /= w_in;
+    const int iy = (int)(pix % h_in);
+    const size_t n = pix / h_in;
+    const size_t o = ((n * 2 * h_in + 2 * iy) * 2 * w_in + 2 * ix) * cpp + cc;
+    const size_t row = (size_t)2 * w_in * cpp;
+    y[o] = v; y[o + cpp] = v; y[o + row] = v; y[o + row + cpp] = v;
+  }
 }
 
 template <typename T>
@@ -112,9 +118,11 @@ int launch_upsample2x(const void* x, void* y, int dtype, int n, int h_in, int w_
   const size_t out_elems = (size_t)n * 4 * h_in * w_in * c;
   if (((size_t)c * es) % 16 == 0) {
     const int cpp = (int)((size_t)c * es / 16);
-    const size_t total = out_elems * es / 16;
-    hipLaunchKernelGGL(upsample2x_vec, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
-                       (const Chunk16*)x, (Chunk16*)y, h_in, w_in, cpp, total);
+    const size_t total_in = out_elems / 4 * es / 16;
+    size_t blocks = (total_in + 255) / 256;
+    if (blocks > 8192) blocks = 8192;   // grid-stride beyond 32 workgroups per compute unit
+    hipLaunchKernelGGL(upsample2x_vec, dim3((unsigned)blocks), dim3(256), 0, s,
+                       (const Chunk16*)x, (Chunk16*)y, h_in, w_in, cpp, total_in);
   } else if (es == 4) {
     hipLaunchKernelGGL(upsample2x_elem<uint32_t>, dim3((unsigned)((out_elems + 255) / 256)), dim3(256), 0, s,
                        (const uint32_t*)x, (uint32_t*)y, h_in, w_in, c, out_elems);
@@ -149,6 +157,17 @@ int launch_transpose(const void* src, int src_dtype, void* dst, int dst_dtype, i
     case WMDEC_BF16: return transpose_s<bf16_t>(src, dst, dst_dtype, batch, rows, cols, src_ld, src_batch_stride, dst_ld, dst_batch_stride, s);
     default: return transpose_s<f16_t>(src, dst, dst_dtype, batch, rows, cols, src_ld, src_batch_stride, dst_ld, dst_batch_stride, s);
   }
+}
+
+__global__ void zero_u32_kernel(unsigned* p, int count) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) p[i] = 0u;
+}
+
+int launch_zero_u32(void* p, int count, hipStream_t s) {
+  hipLaunchKernelGGL(zero_u32_kernel, dim3((unsigned)((count + 63) / 64)), dim3(64), 0, s, (unsigned*)p, count);
+  WMDEC_HIP(hipGetLastError());
+  return WMDEC_OK;
 }
 
 int launch_copy_f32(const float* src, float* dst, size_t count, hipStream_t s) {

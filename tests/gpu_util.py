@@ -43,7 +43,7 @@ def pack(w_oihw, dtype):
 
 def gn_stats(x_dev, groups, eps):
     n, h, w, c = x_dev.shape
-    ws = torch.empty(max(wmdec.gn_stats_workspace_bytes(n, h, w, c, groups), 16), dtype=torch.uint8, device="cuda")
+    ws = torch.zeros(max(wmdec.gn_stats_workspace_bytes(n, h, w, c, groups), 256), dtype=torch.uint8, device="cuda")   # ticket counter starts at zero
     mean = torch.empty(n * groups, dtype=torch.float32, device="cuda")
     rstd = torch.empty(n * groups, dtype=torch.float32, device="cuda")
     wmdec.gn_stats(x_dev, groups, eps, mean, rstd, ws)
