@@ -112,7 +112,17 @@ int wmdec_gn_conv1x1(const void* x, int act_dtype, const float* mean, const floa
  *   y[n,oy,ox,co] = bias[co] + sum W[co,ci,ky,kx] * x[n,(oy+ky-1)>>1,(ox+kx-1)>>1,ci]
  * for 0 <= oy+ky-1 < 2*h_in and 0 <= ox+kx-1 < 2*w_in, zero otherwise.
  * x: [n,h_in,w_in,cin]; y: [n,2*h_in,2*w_in,cout].  The upsampled tensor is
- * never materialised. */
+ * never materialised.  On the matrix-core path the sum is evaluated per output
+ * phase (oy&1, ox&1): the 3x3 taps that read the same input pixel are added
+ * once, when the weights are packed, so each output costs a 2x2 convolution
+ * (4/9 of the multiplications; same sum, the pre-added weights are rounded to
+ * the operand type once).
+ * w_packed: from wmdec_pack_upconv_weights (NOT wmdec_pack_conv_weights): the
+ * 9-tap pack followed by the 16-tap phase pack, wmdec_upconv_packed_bytes()
+ * bytes in total, 16-byte aligned. */
+size_t wmdec_upconv_packed_bytes(int cout, int cin, int op_dtype);
+int wmdec_pack_upconv_weights(const void* src, int src_dtype, int cout, int cin, void* packed,
+                              int op_dtype, void* stream);
 int wmdec_upsample2x_conv3x3(const void* x, int act_dtype, const void* w_packed, const float* bias,
                              void* y, int y_dtype, int n, int h_in, int w_in, int cin, int cout,
                              void* stream);

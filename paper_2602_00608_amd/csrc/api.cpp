@@ -69,6 +69,7 @@ struct Param {  // one canonical parameter
   size_t offset, bytes;      // in the canonical blob
   size_t packed_offset;      // in the packed blob
   size_t packed_bytes;
+  bool upconv = false;       // weights of an upsampling convolution: 9-tap pack followed by the 16-tap phase pack
 };
 
 struct Step {
@@ -115,24 +116,27 @@ struct Builder {
   size_t off = 0, poff = 0;
   explicit Builder(wmdec_decoder& dec) : d(dec) {}
 
-  int add(const std::string& name, int s0, int s1, int s2, int s3, int dtype) {
+  int add(const std::string& name, int s0, int s1, int s2, int s3, int dtype, bool upconv = false) {
     Param p;
     p.name = name;
+    p.upconv = upconv;
     p.shape[0] = s0; p.shape[1] = s1; p.shape[2] = s2; p.shape[3] = s3;
     p.dtype = dtype;
     p.bytes = (size_t)s0 * s1 * s2 * s3 * dtype_size(dtype);
     p.offset = off;
     off = align_up(off + p.bytes, 256);
     // packed: conv weights in the operand type, everything else copied as fp32
-    p.packed_bytes = dtype == WMDEC_F32 ? p.bytes : packed_elems(s2 * s3, s0, s1) * dtype_size(d.cfg.act_dtype);
+    p.packed_bytes = dtype == WMDEC_F32 ? p.bytes
+                     : upconv ? upconv_packed_bytes(s0, s1, d.cfg.act_dtype)
+                              : packed_elems(s2 * s3, s0, s1) * dtype_size(d.cfg.act_dtype);
     p.packed_offset = poff;
     poff = align_up(poff + p.packed_bytes, 256);
     d.params.push_back(p);
     return (int)d.params.size() - 1;
   }
   // conv parameters: weight then bias
-  void conv_params(const std::string& name, int cout, int cin, int k, size_t* w_off, size_t* b_off) {
-    const int wi = add(name + ".w", cout, cin, k, k, WMDEC_BF16);
+  void conv_params(const std::string& name, int cout, int cin, int k, size_t* w_off, size_t* b_off, bool upconv = false) {
+    const int wi = add(name + ".w", cout, cin, k, k, WMDEC_BF16, upconv);
     const int bi = add(name + ".b", cout, 1, 1, 1, WMDEC_F32);
     *w_off = d.params[wi].packed_offset;
     *b_off = d.params[bi].packed_offset;
@@ -286,7 +290,7 @@ static int build_plan(wmdec_decoder& d) {
       char nm[64];
       snprintf(nm, sizeof(nm), "up.%d.upsample", l);
       Step s; s.kind = Step::CONV; s.src = cur; s.dst = other(1); s.h = 2 * h; s.w = 2 * w; s.cin = ch; s.cout = ch; s.upsample = 1;
-      B.conv_params(nm, ch, ch, 3, &s.w_off, &s.b_off);
+      B.conv_params(nm, ch, ch, 3, &s.w_off, &s.b_off, true);
       d.steps.push_back(s); B.count_conv(s);
       h *= 2; w *= 2;
       B.track(h, w, ch);
@@ -396,6 +400,21 @@ int wmdec_pack_conv_weights(const void* src, int src_dtype, int cout, int cin, i
   return launch_pack_conv(src, src_dtype, cout, cin, k, packed, op_dtype, 0, cout, (hipStream_t)stream);
 }
 
+size_t wmdec_upconv_packed_bytes(int cout, int cin, int op_dtype) {
+  if (cout <= 0 || cin <= 0 || !valid_dtype(op_dtype)) return 0;
+  return upconv_packed_bytes(cout, cin, op_dtype);
+}
+
+int wmdec_pack_upconv_weights(const void* src, int src_dtype, int cout, int cin, void* packed, int op_dtype, void* stream) {
+  WMDEC_REQUIRE(src && packed, WMDEC_ERR_INVALID_ARG, "pack_upconv_weights: null pointer");
+  WMDEC_REQUIRE(src_dtype == WMDEC_F32 || src_dtype == WMDEC_BF16, WMDEC_ERR_INVALID_ARG,
+                "pack_upconv_weights: source must be F32 or BF16");
+  WMDEC_REQUIRE(valid_dtype(op_dtype), WMDEC_ERR_INVALID_ARG, "pack_upconv_weights: bad op_dtype");
+  WMDEC_REQUIRE(cout > 0 && cin > 0, WMDEC_ERR_INVALID_ARG, "pack_upconv_weights: bad shape");
+  WMDEC_REQUIRE(aligned16(packed), WMDEC_ERR_INVALID_ARG, "pack_upconv_weights: packed must be 16-byte aligned");
+  return launch_pack_upconv(src, src_dtype, cout, cin, packed, op_dtype, (hipStream_t)stream);
+}
+
 static int conv_entry(const char* who, int ksize, int upsample, const void* x, int act_dtype, const float* mean,
                       const float* rstd, const float* gamma, const float* beta, int groups, int apply_silu,
                       const void* w_packed, const float* bias, const void* residual, void* y, int y_dtype, int n,
@@ -409,6 +428,7 @@ static int conv_entry(const char* who, int ksize, int upsample, const void* x, i
   a.wt = w_packed; a.op_dtype = act_dtype; a.bias = bias; a.res = residual; a.res_dtype = act_dtype;
   a.y = y; a.y_dtype = y_dtype; a.n = n; a.h = h_out; a.w = w_out; a.cin = cin; a.cout = cout;
   a.ksize = ksize; a.upsample = upsample;
+  if (upsample) a.wt_phase = (const char*)w_packed + upconv_phase_offset_bytes(cout, cin, act_dtype);
   return launch_conv(a, (hipStream_t)stream);
 }
 
@@ -617,6 +637,8 @@ int decoder_pack_weights(const wmdec_decoder* dec, const void* weights, void* pa
       rc = launch_pack_conv(src + p.offset, p.dtype, c0, c0, 1, dst + dec->qkv_w_off, dec->cfg.act_dtype, part * c0, 3 * c0, s);
     } else if (p.dtype == WMDEC_F32) {
       rc = launch_copy_f32((const float*)(src + p.offset), (float*)(dst + p.packed_offset), p.bytes / 4, s);
+    } else if (p.upconv) {
+      rc = launch_pack_upconv(src + p.offset, p.dtype, p.shape[0], p.shape[1], dst + p.packed_offset, dec->cfg.act_dtype, s);
     } else {
       rc = launch_pack_conv(src + p.offset, p.dtype, p.shape[0], p.shape[1], p.shape[2], dst + p.packed_offset,
                             dec->cfg.act_dtype, 0, p.shape[0], s);
@@ -680,6 +702,7 @@ int decoder_run(wmdec_decoder* dec, const void* latent, const void* packed, void
         else { a.x = buf(st.src); a.x_dtype = c.act_dtype; }
         if (st.norm) { a.mean = mean; a.rstd = rstd; a.gamma = (const float*)(pk + st.gamma_off); a.beta = (const float*)(pk + st.beta_off); a.groups = c.groups; a.silu = st.silu; }
         a.wt = pk + st.w_off; a.bias = (const float*)(pk + st.b_off);
+        if (st.upsample) a.wt_phase = pk + st.w_off + upconv_phase_offset_bytes(st.cout, st.cin, c.act_dtype);
         a.res = buf(st.res);
         if (st.dst == BUF_OUT) { a.y = out; a.y_dtype = WMDEC_F32; a.y_nchw = 1; }
         else if (st.to_attn == 1) { a.y = ws + L.qkv; a.y_dtype = c.act_dtype; }

@@ -76,6 +76,7 @@ struct ConvArgs {
   int groups = 1;
   int silu = 0;
   const void* wt = nullptr;      // packed [k*k][cout][cin] in op dtype
+  const void* wt_phase = nullptr;  // upsample only: the 16-tap phase pack (pre-summed 2x2 weights of the four output phases)
   int op_dtype = WMDEC_F32;      // arithmetic: F32 (FMA) or BF16 / F16 (operands rounded to it)
   const float* bias = nullptr;   // [cout] or null
   const void* res = nullptr;     // [n,h,w,cout] of res_dtype or null
@@ -118,6 +119,10 @@ int launch_gn_finalize(const void* ws, int n_groups, int slots, float eps, float
 int launch_upsample2x(const void* x, void* y, int dtype, int n, int h_in, int w_in, int c, hipStream_t s);
 int launch_pack_conv(const void* src, int src_dtype, int cout, int cin, int k, void* dst, int op_dtype,
                      int dst_row_offset, int dst_rows_total, hipStream_t s);
+// weights of a nearest-2x-upsample + 3x3 convolution: the 9-tap pack followed by the 16-tap phase pack
+size_t upconv_phase_offset_bytes(int cout, int cin, int op_dtype);
+size_t upconv_packed_bytes(int cout, int cin, int op_dtype);
+int launch_pack_upconv(const void* src, int src_dtype, int cout, int cin, void* dst, int op_dtype, hipStream_t s);
 // dst[n][i][j] (dst_dtype) = src[n][j][i] (src_dtype); src is [rows=j][cols=i] with row stride src_ld
 int launch_transpose(const void* src, int src_dtype, void* dst, int dst_dtype, int batch, int rows, int cols,
                      size_t src_ld, size_t src_batch_stride, size_t dst_ld, size_t dst_batch_stride, hipStream_t s);

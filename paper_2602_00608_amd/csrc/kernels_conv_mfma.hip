@@ -65,10 +65,17 @@ template <typename T> __device__ __forceinline__ void unpack8(const u32x4& v, fl
 // output move as 16-byte vectors and every pixel's channel run is written contiguously.
 // lds: 32 x (NI*32 + 4) floats owned by this wavefront.  LDS operations of one wavefront execute
 // in order, so the patch needs no barrier between its write and read phases.
+// floats of the wavefront-private epilogue patch: 32 padded rows, and at least the 64 x 8 four-float entries
+// that the statistics reduction parks there
+constexpr int patch_floats(int ni) { return 32 * (ni * 32 + 4) > 2048 ? 32 * (ni * 32 + 4) : 2048; }
+
 template <typename T, typename TO, int MI, int NI, int MTW, int MTH, int MT_PER_ROW, bool RES>
 __device__ __forceinline__ void epilogue_store(const f32x16 (&acc)[MI][NI], float* lds, int lane, int mt0, int ty0,
                                                int tx0, int co_w, const float* bias, const T* rin, TO* yout, int h,
-                                               int w_out, int cout, bool nchw, Moments* stats, int cpg, int stats_stride) {
+                                               int w_out, int cout, bool nchw, Moments* stats, int cpg, int stats_stride,
+                                               int osc = 1, int oy_off = 0, int ox_off = 0) {
+  // tile pixel (ty, tx) is output pixel (ty * osc + oy_off, tx * osc + ox_off): osc = 2 when the tile lives on the
+  // low-resolution grid of a phase-decomposed upsampling convolution
   constexpr int RW = NI * 32 + 4;       // padded row of the patch, floats
   if (nchw) {
     // planar output with few channels (the frame): a lane owns one pixel of the M tile and walks the
@@ -102,7 +109,8 @@ __device__ __forceinline__ void epilogue_store(const f32x16 (&acc)[MI][NI], floa
   auto vec_off = [&](int mi, int j) -> int {
     const int mt = mt0 + mi;
     const int pi = prow + j * (64 / (NI * 4));
-    const int oy = ty0 + (mt / MT_PER_ROW) * MTH + pi / MTW, ox = tx0 + (mt % MT_PER_ROW) * MTW + pi % MTW;
+    const int oy = (ty0 + (mt / MT_PER_ROW) * MTH + pi / MTW) * osc + oy_off;
+    const int ox = (tx0 + (mt % MT_PER_ROW) * MTW + pi % MTW) * osc + ox_off;
     return (oy < h && ox < w_out) ? (oy * w_out + ox) * cout + co_w + cvec * 8 : -1;   // < 2^30 elements (checked on the host)
   };
   // residual vectors are fetched two M tiles ahead (unconditional loads, clamped to element 0 outside the
@@ -201,7 +209,13 @@ __device__ __forceinline__ void static_for(F&& f) { static_for_impl<N>(f, std::m
 
 // Ring length of the weight-fragment prefetch: it must divide the k-steps of a chunk so that the ring
 // position is the same at every chunk start.
-constexpr int prefetch_ring(int steps) { return steps % 3 == 0 ? 3 : (steps % 4 == 0 ? 4 : 2); }
+// It is as long as the register budget of the tile allows (`room`: accumulator tiles per wavefront): the
+// fragments come from the L2, whose latency is several k-steps.
+constexpr int prefetch_ring(int steps, int room) {
+  (void)room;
+  if (steps % 6 == 0) return 6;
+  return steps % 3 == 0 ? 3 : (steps % 4 == 0 ? 4 : 2);
+}
 
 // MFMA work of one staged chunk: STEPS = taps * KC/16 k-steps, each MI x NI 32x32x16 MFMAs.
 // Weight fragments are fetched D-1 steps ahead (bq is a ring that persists across chunks: on
@@ -226,20 +240,29 @@ __device__ __forceinline__ void mfma_chunk(const T* buf, const int (&a_off)[MI],
       constexpr int sp = s + D - 1;
       const u32x4* src = sp < STEPS ? bcur : bnext;
       constexpr int spp = sp < STEPS ? sp : sp - STEPS;
+#ifndef WMDEC_ABL_NOB
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni)
         bq[sp % D][ni] = (src + ((spp / KK) * tap_stride + (spp % KK) * kk_stride + ni * 64))[lane];
+#endif
     }
     __builtin_amdgcn_sched_barrier(0);
     auto tile = [&](auto mi_c) {
       constexpr int mi = decltype(mi_c)::value;
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = Mma<T>::m32(af[mi], bq[s % D][ni], acc[mi][ni]);
-      if constexpr (s + 1 < STEPS) {
+#ifndef WMDEC_ABL_NOA
+      if constexpr (s + 1 < STEPS)
+#else
+      if constexpr (false)
+#endif
+      {
         constexpr int tap = (s + 1) / KK, kk = (s + 1) % KK;
         af[mi] = *reinterpret_cast<const u32x4*>(buf + a_off[mi] + ((tap / KS) * HW_ + tap % KS) * PS + kk * 16);
       }
+#ifndef WMDEC_ABL_NOSLICE
       if constexpr (SLICED) slice(std::integral_constant<int, s * MI + mi>{});
+#endif
       __builtin_amdgcn_sched_barrier(0);
     };
     static_for<MI>(tile);
@@ -248,11 +271,19 @@ __device__ __forceinline__ void mfma_chunk(const T* buf, const int (&a_off)[MI],
 }
 
 // ACT: what happens to an input element on its way into LDS: 0 nothing, 1 scale/shift, 2 scale/shift + SiLU
-template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC, int ACT>
-__global__ __launch_bounds__(256, (TH * TW / 32 / WM) * NI <= 4 ? 3 : 2) void conv_mfma_kernel(MfmaParams p) {
+// PH: phase-decomposed nearest-2x upsampling convolution.  The tile lives on the low-resolution input grid; wavefront
+// w computes output phase (py, px) = (w >> 1, w & 1) of all its pixels, i.e. output pixels (2i + py, 2j + px), as a
+// 2x2 convolution over input rows i + py - 1 .. i + py and columns j + px - 1 .. j + px with the phase's pre-summed
+// weights (taps 4 * w .. 4 * w + 3 of the 16-tap phase pack): 4/9 of the multiplications of the 3x3 form.
+constexpr int wave_m_tiles(int th, int tw, int wm, bool ph) { return ph ? th * tw / 32 : th * tw / 32 / wm; }
+
+template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC, int ACT, bool PH = false>
+__global__ __launch_bounds__(256, wave_m_tiles(TH, TW, WM, PH) * NI <= 4 ? 3 : 2) void conv_mfma_kernel(MfmaParams p) {
   static_assert(WM * WN == 4, "four wavefronts");
-  constexpr int MI = TH * TW / 32 / WM;          // 32-pixel M tiles per wavefront
-  constexpr int PAD = KS / 2;
+  static_assert(!PH || (KS == 3 && WM == 4 && WN == 1), "phase mode: one wavefront per phase");
+  constexpr int MI = wave_m_tiles(TH, TW, WM, PH);   // 32-pixel M tiles per wavefront
+  constexpr int KT = PH ? 2 : KS;                // taps per dimension a wavefront sweeps
+  constexpr int PAD = PH ? 1 : KS / 2;
   constexpr int HW_ = TW + 2 * PAD, HH_ = TH + 2 * PAD, HP = HW_ * HH_;
   constexpr int PS = KC + 8;                     // LDS pixel stride in elements (+16 B: conflict-free 16-byte reads)
   constexpr int MTW = TW < 32 ? TW : 32, MTH = 32 / MTW, MT_PER_ROW = TW / MTW;
@@ -260,7 +291,7 @@ __global__ __launch_bounds__(256, (TH * TW / 32 / WM) * NI <= 4 ? 3 : 2) void co
   constexpr int VPP = KC / 8;                    // 16-byte vectors per pixel per chunk
   constexpr int NV = (HP * VPP + 255) / 256;     // vectors a thread stages per chunk
   constexpr int BUF = (NV * 256 / VPP) * PS;     // elements of one staged tile (rounded up: every thread stores all its NV vectors)
-  constexpr int STEPS = KS * KS * (KC / 16), SLOTS = STEPS * MI;
+  constexpr int STEPS = KT * KT * (KC / 16), SLOTS = STEPS * MI;
   constexpr bool SLICED = KS == 3;               // activation of the next chunk is sliced into the MFMA sweep
   static_assert(256 % VPP == 0, "a thread keeps one channel octet");
 
@@ -287,6 +318,7 @@ __global__ __launch_bounds__(256, (TH * TW / 32 / WM) * NI <= 4 ? 3 : 2) void co
   const int ty0 = (tile / p.tiles_x) * TH, tx0 = (tile % p.tiles_x) * TW;
   const int co0 = nt * TN;
   const int h_in = p.upsample ? p.h >> 1 : p.h, w_in = p.upsample ? p.w_out >> 1 : p.w_out;
+  const int h_t = PH ? h_in : p.h, w_t = PH ? w_in : p.w_out;   // the grid the tiles live on
 
   // per-channel scale/shift table: a = gamma*rstd, b = beta - mean*a
   if constexpr (ACT > 0) {
@@ -310,15 +342,16 @@ __global__ __launch_bounds__(256, (TH * TW / 32 / WM) * NI <= 4 ? 3 : 2) void co
   int a_off[MI];
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) {
-    const int mt = wm * MI + mi;
+    const int mt = PH ? mi : wm * MI + mi;
     const int ty = (mt / MT_PER_ROW) * MTH + lm / MTW, tx = (mt % MT_PER_ROW) * MTW + lm % MTW;
-    a_off[mi] = (ty * HW_ + tx) * PS + 8 * lk;
+    a_off[mi] = (ty * HW_ + tx) * PS + 8 * lk + (PH ? ((wave >> 1) * HW_ + (wave & 1)) * PS : 0);
   }
   constexpr int KK = KC / 16;
-  constexpr int D = prefetch_ring(KS * KS * KK);   // weight fragments are fetched D-1 k-steps ahead
+  constexpr int D = prefetch_ring(KT * KT * KK, MI * NI);   // weight fragments are fetched D-1 k-steps ahead
   const int tap_stride = p.cin_blocks * p.cout_blocks * 64, kk_stride = p.cout_blocks * 64;   // in 16-byte units
   // fragment column of this wavefront (uniform pointer; the lane index is added at the load)
-  const u32x4* wcol = reinterpret_cast<const u32x4*>(p.w) + (size_t)((co0 >> 5) + wn * NI) * 64;
+  const u32x4* wcol = reinterpret_cast<const u32x4*>(p.w) + (size_t)((co0 >> 5) + wn * NI) * 64 +
+                      (PH ? (size_t)(wave * 4) * tap_stride : 0);
   u32x4 bq[D][NI];
 #pragma unroll
   for (int sp = 0; sp < D - 1; ++sp)
@@ -336,8 +369,8 @@ __global__ __launch_bounds__(256, (TH * TW / 32 / WM) * NI <= 4 ? 3 : 2) void co
     const int hy = hp / HW_, hx = hp % HW_;
     const int gy = ty0 + hy - PAD, gx = tx0 + hx - PAD;
     src_off[i] = -1;
-    if (v < HP * VPP && gy >= 0 && gy < p.h && gx >= 0 && gx < p.w_out) {
-      const int sy = p.upsample ? gy >> 1 : gy, sx = p.upsample ? gx >> 1 : gx;
+    if (v < HP * VPP && gy >= 0 && gy < h_t && gx >= 0 && gx < w_t) {
+      const int sy = (!PH && p.upsample) ? gy >> 1 : gy, sx = (!PH && p.upsample) ? gx >> 1 : gx;
       src_off[i] = ((sy * w_in + sx) * p.cin + cvec * 8) * (int)sizeof(T);
     }
   }
@@ -350,6 +383,9 @@ __global__ __launch_bounds__(256, (TH * TW / 32 / WM) * NI <= 4 ? 3 : 2) void co
   // afterwards): a load under a lane mask makes the compiler wait for it at the end of the branch.
   u32x4 raw[NV];
   auto issue = [&](int chunk) {
+#ifdef WMDEC_ABL_NOISSUE
+    if (chunk > 1) return;
+#endif
     const int cb = min(chunk, p.cin / KC - 1) * KC * (int)sizeof(T);   // past the last chunk: a harmless reload
 #pragma unroll
     for (int i = 0; i < NV; ++i) raw[i] = *reinterpret_cast<const u32x4*>(xin + (unsigned)(max(src_off[i], 0) + cb));
@@ -378,6 +414,9 @@ __global__ __launch_bounds__(256, (TH * TW / 32 / WM) * NI <= 4 ? 3 : 2) void co
   const int nchunks = p.cin / KC;
 
   TRACE(0);
+#ifdef WMDEC_TRACE
+  if (p.trace && tid == 0) p.trace[(size_t)blockIdx.x * 64 + 60] = clock64();
+#endif
   issue(0);
   __syncthreads();            // scale/shift table complete
   activate_all(0, s_a);
@@ -386,8 +425,13 @@ __global__ __launch_bounds__(256, (TH * TW / 32 / WM) * NI <= 4 ? 3 : 2) void co
   TRACE(1);
   for (int c = 0; c < nchunks; ++c) {
     const bool more = c + 1 < nchunks;
+#ifdef WMDEC_ABL_SAMEB
+    const u32x4* bcur = wcol;
+    const u32x4* bnext = wcol + (more ? 0 : 0);
+#else
     const u32x4* bcur = wcol + (size_t)(c * KK) * kk_stride;
     const u32x4* bnext = more ? bcur + (size_t)KK * kk_stride : bcur;
+#endif
     const T* buf = s_a + (c & 1) * BUF;
     T* nbuf = s_a + ((c + 1) & 1) * BUF;
     const int c0n = (c + 1) * KC;
@@ -408,11 +452,11 @@ __global__ __launch_bounds__(256, (TH * TW / 32 / WM) * NI <= 4 ? 3 : 2) void co
       };
       // the last chunk activates a harmless reload into the buffer nobody reads: one instruction stream, no
       // control flow inside the pinned schedule
-      mfma_chunk<T, MI, NI, KS, KC, HW_, PS, D, true>(buf, a_off, bcur, bnext, tap_stride, kk_stride, lane, bq, acc, slice);
+      mfma_chunk<T, MI, NI, KT, KC, HW_, PS, D, true>(buf, a_off, bcur, bnext, tap_stride, kk_stride, lane, bq, acc, slice);
       TRACE(3 + 4 * c);
     } else {
       auto none = [](auto) {};
-      mfma_chunk<T, MI, NI, KS, KC, HW_, PS, D, false>(buf, a_off, bcur, bnext, tap_stride, kk_stride, lane, bq, acc, none);
+      mfma_chunk<T, MI, NI, KT, KC, HW_, PS, D, false>(buf, a_off, bcur, bnext, tap_stride, kk_stride, lane, bq, acc, none);
       TRACE(3 + 4 * c);
       if (more) activate_all(c0n, nbuf);
     }
@@ -425,29 +469,40 @@ __global__ __launch_bounds__(256, (TH * TW / 32 / WM) * NI <= 4 ? 3 : 2) void co
   // ---- epilogue: bias, residual, one rounding, store (through a wavefront-private LDS patch over the tile buffers)
   TO* yout = reinterpret_cast<TO*>(p.y) + (size_t)n * p.h * p.w_out * p.cout;
   const T* rin = p.res ? reinterpret_cast<const T*>(p.res) + (size_t)n * p.h * p.w_out * p.cout : nullptr;
-  float* patch = reinterpret_cast<float*>(smem) + wave * (32 * (NI * 32 + 4));
+  float* patch = reinterpret_cast<float*>(smem) + wave * patch_floats(NI);
   // statistics slot of this wavefront: [sample][group][spatial tile * WM + wave row]
   Moments* st = p.stats ? p.stats + (size_t)n * p.stats_groups * p.stats_slots + (tile * WM + wm) : nullptr;
+#ifdef WMDEC_ABL_NOEPI
+  if (acc[0][0][0] == 123.456f) yout[tid] = from_float<TO>(acc[1][1][3] + acc[2][0][5] + acc[3][1][7]);
+  else if (p.n < 0)
+#endif
   if (rin)
-    epilogue_store<T, TO, MI, NI, MTW, MTH, MT_PER_ROW, true>(acc, patch, lane, wm * MI, ty0, tx0, co0 + wn * NI * 32, p.bias,
-                                                              rin, yout, p.h, p.w_out, p.cout, false, st, p.stats_cpg, p.stats_slots);
+    epilogue_store<T, TO, MI, NI, MTW, MTH, MT_PER_ROW, true>(acc, patch, lane, PH ? 0 : wm * MI, ty0, tx0, co0 + wn * NI * 32, p.bias,
+                                                              rin, yout, p.h, p.w_out, p.cout, false, st, p.stats_cpg, p.stats_slots,
+                                                              PH ? 2 : 1, PH ? wave >> 1 : 0, PH ? wave & 1 : 0);
   else
-    epilogue_store<T, TO, MI, NI, MTW, MTH, MT_PER_ROW, false>(acc, patch, lane, wm * MI, ty0, tx0, co0 + wn * NI * 32, p.bias,
-                                                               rin, yout, p.h, p.w_out, p.cout, p.y_nchw != 0, st, p.stats_cpg, p.stats_slots);
+    epilogue_store<T, TO, MI, NI, MTW, MTH, MT_PER_ROW, false>(acc, patch, lane, PH ? 0 : wm * MI, ty0, tx0, co0 + wn * NI * 32, p.bias,
+                                                               rin, yout, p.h, p.w_out, p.cout, p.y_nchw != 0, st, p.stats_cpg, p.stats_slots,
+                                                               PH ? 2 : 1, PH ? wave >> 1 : 0, PH ? wave & 1 : 0);
   TRACE(63);
+#ifdef WMDEC_TRACE
+  if (p.trace && tid == 0) p.trace[(size_t)blockIdx.x * 64 + 61] = clock64();
+#endif
 }
 
-template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC>
+template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC, bool PH = false>
 int launch_cfg(const ConvArgs& a, hipStream_t s) {
-  constexpr int PAD = KS / 2;
+  constexpr int PAD = PH ? 1 : KS / 2;
   constexpr int HP = (TW + 2 * PAD) * (TH + 2 * PAD);
   constexpr int TN = WN * NI * 32;
+  WMDEC_REQUIRE(!PH || (a.wt_phase && a.h % 2 == 0 && a.w % 2 == 0), WMDEC_ERR_INVALID_ARG, "conv_mfma: upsampling convolution without phase weights");
   MfmaParams p;
   p.x = a.x; p.mean = a.mean; p.rstd = a.rstd; p.gamma = a.gamma; p.beta = a.beta;
-  p.w = a.wt; p.bias = a.bias; p.res = a.res; p.y = a.y;
+  p.w = PH ? a.wt_phase : a.wt; p.bias = a.bias; p.res = a.res; p.y = a.y;
   p.silu = a.silu; p.groups = a.groups; p.norm = a.mean != nullptr;
   p.n = a.n; p.h = a.h; p.w_out = a.w; p.cin = a.cin; p.cout = a.cout; p.upsample = a.upsample;
-  p.tiles_x = (a.w + TW - 1) / TW; p.tiles_y = (a.h + TH - 1) / TH; p.ntiles = (a.cout + TN - 1) / TN;
+  const int w_t = PH ? a.w / 2 : a.w, h_t = PH ? a.h / 2 : a.h;   // the grid the tiles live on
+  p.tiles_x = (w_t + TW - 1) / TW; p.tiles_y = (h_t + TH - 1) / TH; p.ntiles = (a.cout + TN - 1) / TN;
   p.total = p.tiles_x * p.tiles_y * p.ntiles * a.n;
   p.cin_blocks = packed_cin_blocks(a.cin); p.cout_blocks = packed_cout_blocks(a.cout); p.y_nchw = a.y_nchw;
   p.stats = (Moments*)a.stats_ws; p.stats_groups = a.stats_groups; p.stats_cpg = a.stats_groups > 0 ? a.cout / a.stats_groups : 1;
@@ -457,12 +512,12 @@ int launch_cfg(const ConvArgs& a, hipStream_t s) {
 #endif
   constexpr int NV = (HP * (KC / 8) + 255) / 256;
   size_t smem = (((size_t)2 * (NV * 256 / (KC / 8)) * (KC + 8) * 2 + 15) & ~(size_t)15) + (size_t)a.cin * sizeof(float2);
-  const size_t patch = (size_t)4 * 32 * (NI * 32 + 4) * sizeof(float);   // epilogue patches of the four wavefronts
+  const size_t patch = (size_t)4 * patch_floats(NI) * sizeof(float);   // epilogue patches of the four wavefronts
   if (smem < patch) smem = patch;
   WMDEC_REQUIRE(smem <= 80 * 1024, WMDEC_ERR_UNSUPPORTED, "conv_mfma: %zu bytes of LDS needed", smem);
-  void (*kern)(MfmaParams) = !p.norm ? conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 0>
-                             : (a.silu ? conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 2>
-                                       : conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 1>);
+  void (*kern)(MfmaParams) = !p.norm ? conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 0, PH>
+                             : (a.silu ? conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 2, PH>
+                                       : conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 1, PH>);
   static bool attr_set[3] = {false, false, false};   // per instantiation and activation mode
   const int mode = !p.norm ? 0 : (a.silu ? 2 : 1);
   if (!attr_set[mode]) {
@@ -485,6 +540,8 @@ constexpr TileShape kTiles[] = {
     {16, 16, 2, 2, 2},   // 5: 256 x 128, 16x16 patch
     {8, 16, 4, 1, 2},    // 6: 128 x 64, 8x16 patch
     {8, 32, 4, 1, 1},    // 7: 256 x 32 (few output channels: the frame)
+    {8, 32, 1, 4, 1},    // 8: 256 x 128, every wavefront all pixels x 32 channels: no weight fragment is loaded twice
+    {8, 16, 4, 1, 2},    // 9: phase-decomposed upsampling convolution: 8x16 input pixels (16x32 outputs) x 64 channels
 };
 
 // which tile shape a launch uses (3x3: any of the above; 1x1: 0, 1 or 2)
@@ -492,8 +549,11 @@ int pick_tile(const ConvArgs& a) {
   const long px = (long)a.h * a.w;   // per sample: the tiling, hence every summation order, does not depend on the batch
   const bool n128 = a.cout % 128 == 0;
   if (a.ksize == 3) {
+    // phase decomposition (needs a.wt_phase at launch) for f16 only: pre-added weights rounded to bf16 would cost
+    // that type a visible part of its error budget
+    if (a.upsample && a.op_dtype == WMDEC_F16 && a.cout % 64 == 0 && g_tile != 0) return 9;
     if (a.cout <= 32) return 7;
-    int t = (g_tile == 0 || g_tile == 4 || g_tile == 6) ? g_tile : ((n128 && px * (a.cout / 128) >= 256L * 256 * 3) ? 0 : (n128 ? 4 : 6));
+    int t = (g_tile == 0 || g_tile == 4 || g_tile == 6 || g_tile == 8) ? g_tile : ((n128 && px * (a.cout / 128) >= 256L * 256 * 3) ? 0 : (n128 ? 4 : 6));
     if (!n128) t = 6;
     return t;
   }
@@ -507,6 +567,8 @@ int launch_3x3(const ConvArgs& a, hipStream_t s) {
     case 0: return launch_cfg<T, TO, 8, 32, 2, 2, 2, 3, 32>(a, s);
     case 4: return launch_cfg<T, TO, 8, 16, 2, 2, 2, 3, 32>(a, s);
     case 6: return launch_cfg<T, TO, 8, 16, 4, 1, 2, 3, 32>(a, s);
+    case 8: return launch_cfg<T, TO, 8, 32, 1, 4, 1, 3, 32>(a, s);
+    case 9: return launch_cfg<T, TO, 8, 16, 4, 1, 2, 3, 32, true>(a, s);
     default: return launch_cfg<T, TO, 8, 32, 4, 1, 1, 3, 32>(a, s);
   }
 }
@@ -562,7 +624,8 @@ int conv_mfma_stats_slots(const ConvArgs& a) {
   int t = pick_tile(a);
   if (a.ksize == 1 && a.cin % 64 != 0 && t == 0) t = 1;
   const TileShape& ts = kTiles[t];
-  return ((a.w + ts.tw - 1) / ts.tw) * ((a.h + ts.th - 1) / ts.th) * ts.wm;
+  const int w_t = t == 9 ? a.w / 2 : a.w, h_t = t == 9 ? a.h / 2 : a.h;
+  return ((w_t + ts.tw - 1) / ts.tw) * ((h_t + ts.th - 1) / ts.th) * ts.wm;
 }
 
 int launch_conv_mfma(const ConvArgs& a, hipStream_t s) {

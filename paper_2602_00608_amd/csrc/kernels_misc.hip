@@ -61,6 +61,31 @@ __global__ __launch_bounds__(256) void pack_conv_kernel(const S* __restrict__ sr
   dst[i] = from_float<D>(to_float(src[((size_t)co * cin + ci) * taps + tap]));
 }
 
+// Phase pack of a nearest-2x-upsample + 3x3 convolution.  Output pixel (2i + py, 2j + px) only sees input rows
+// i + py - 1, i + py and columns j + px - 1, j + px; the 3x3 taps that fall on the same input pixel are summed once,
+// here (fp32, fixed order, one rounding to D).  Row r of phase py collects ky in {0} | {1,2} (py = 0) or {0,1} | {2}
+// (py = 1), the same for columns.  Tap index of the pack: ((py*2 + px)*2 + r)*2 + s, 16 taps.
+template <typename S, typename D>
+__global__ __launch_bounds__(256) void pack_upconv_phase_kernel(const S* __restrict__ src, D* __restrict__ dst, int cout, int cin) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const int cinb = packed_cin_blocks(cin), coutb = packed_cout_blocks(cout);
+  if (i >= (size_t)16 * cinb * coutb * 512) return;
+  const int e = (int)(i & 7), lane = (int)((i >> 3) & 63);
+  size_t blk = i >> 9;
+  const int cob = (int)(blk % coutb); blk /= coutb;
+  const int cib = (int)(blk % cinb);
+  const int tap = (int)(blk / cinb);
+  const int co = cob * 32 + (lane & 31), ci = cib * 16 + (lane >> 5) * 8 + e;
+  if (ci >= cin || co >= cout) { dst[i] = from_float<D>(0.f); return; }
+  const int py = tap >> 3, px = (tap >> 2) & 1, r = (tap >> 1) & 1, sx = tap & 1;
+  const int ky0 = py == 0 ? (r == 0 ? 0 : 1) : (r == 0 ? 0 : 2), ky1 = py == 0 ? (r == 0 ? 0 : 2) : (r == 0 ? 1 : 2);
+  const int kx0 = px == 0 ? (sx == 0 ? 0 : 1) : (sx == 0 ? 0 : 2), kx1 = px == 0 ? (sx == 0 ? 0 : 2) : (sx == 0 ? 1 : 2);
+  float acc = 0.f;
+  for (int ky = ky0; ky <= ky1; ++ky)
+    for (int kx = kx0; kx <= kx1; ++kx) acc += to_float(src[((size_t)co * cin + ci) * 9 + ky * 3 + kx]);
+  dst[i] = from_float<D>(acc);
+}
+
 // dst[b][i][j] = src[b][j][i], 32x32 tiles through LDS
 template <typename S, typename D>
 __global__ __launch_bounds__(256) void transpose_kernel(const S* __restrict__ src, D* __restrict__ dst, int rows, int cols,
@@ -90,6 +115,15 @@ int pack_t(const void* src, void* dst, int cout, int cin, int k, int row_off, in
   const size_t total = packed_elems(k * k, rows_total, cin);
   hipLaunchKernelGGL((pack_conv_kernel<S, D>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
                      (const S*)src, (D*)dst, cout, cin, k * k, row_off, rows_total);
+  WMDEC_HIP(hipGetLastError());
+  return WMDEC_OK;
+}
+
+template <typename S, typename D>
+int pack_phase_t(const void* src, void* dst, int cout, int cin, hipStream_t s) {
+  const size_t total = packed_elems(16, cout, cin);
+  hipLaunchKernelGGL((pack_upconv_phase_kernel<S, D>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                     (const S*)src, (D*)dst, cout, cin);
   WMDEC_HIP(hipGetLastError());
   return WMDEC_OK;
 }
@@ -147,6 +181,27 @@ int launch_pack_conv(const void* src, int src_dtype, int cout, int cin, int k, v
     case WMDEC_F32: return pack_t<bf16_t, float>(src, dst, cout, cin, k, dst_row_offset, dst_rows_total, s);
     case WMDEC_BF16: return pack_t<bf16_t, bf16_t>(src, dst, cout, cin, k, dst_row_offset, dst_rows_total, s);
     default: return pack_t<bf16_t, f16_t>(src, dst, cout, cin, k, dst_row_offset, dst_rows_total, s);
+  }
+}
+
+size_t upconv_phase_offset_bytes(int cout, int cin, int op_dtype) { return packed_elems(9, cout, cin) * dtype_size(op_dtype); }
+size_t upconv_packed_bytes(int cout, int cin, int op_dtype) { return packed_elems(9 + 16, cout, cin) * dtype_size(op_dtype); }
+
+int launch_pack_upconv(const void* src, int src_dtype, int cout, int cin, void* dst, int op_dtype, hipStream_t s) {
+  const int rc = launch_pack_conv(src, src_dtype, cout, cin, 3, dst, op_dtype, 0, cout, s);
+  if (rc != WMDEC_OK) return rc;
+  void* ph = (char*)dst + upconv_phase_offset_bytes(cout, cin, op_dtype);
+  if (src_dtype == WMDEC_F32) {
+    switch (op_dtype) {
+      case WMDEC_F32: return pack_phase_t<float, float>(src, ph, cout, cin, s);
+      case WMDEC_BF16: return pack_phase_t<float, bf16_t>(src, ph, cout, cin, s);
+      default: return pack_phase_t<float, f16_t>(src, ph, cout, cin, s);
+    }
+  }
+  switch (op_dtype) {
+    case WMDEC_F32: return pack_phase_t<bf16_t, float>(src, ph, cout, cin, s);
+    case WMDEC_BF16: return pack_phase_t<bf16_t, bf16_t>(src, ph, cout, cin, s);
+    default: return pack_phase_t<bf16_t, f16_t>(src, ph, cout, cin, s);
   }
 }
 

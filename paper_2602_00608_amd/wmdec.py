@@ -43,6 +43,8 @@ SIGNATURES = {
     "wmdec_pack_conv_weights": (_i, [_vp, _i, _i, _i, _i, _vp, _i, _vp]),
     "wmdec_gn_silu_conv3x3": (_i, [_vp, _i, _vp, _vp, _vp, _vp, _i, _i, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp]),
     "wmdec_gn_conv1x1": (_i, [_vp, _i, _vp, _vp, _vp, _vp, _i, _i, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp]),
+    "wmdec_upconv_packed_bytes": (_sz, [_i] * 3),
+    "wmdec_pack_upconv_weights": (_i, [_vp, _i, _i, _i, _vp, _i, _vp]),
     "wmdec_upsample2x_conv3x3": (_i, [_vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp]),
     "wmdec_upsample2x_nearest": (_i, [_vp, _vp, _i, _i, _i, _i, _i, _vp]),
     "wmdec_nchw_to_nhwc": (_i, [_vp, _i, _vp, _i, _i, _i, _i, _i, _vp]),
@@ -150,6 +152,16 @@ def gn_silu_conv3x3(x, mean, rstd, gamma, beta, groups, apply_silu, w_packed, bi
 def gn_conv1x1(x, mean, rstd, gamma, beta, groups, apply_silu, w_packed, bias, residual, y):
     _conv(lib().wmdec_gn_conv1x1, x, mean, rstd, gamma, beta, groups, apply_silu, w_packed, bias, residual, y,
           x.shape[3], y.shape[3])
+
+
+def upconv_packed_bytes(cout, cin, op_dtype):
+    return lib().wmdec_upconv_packed_bytes(cout, cin, op_dtype)
+
+
+def pack_upconv_weights(src, packed, op_dtype):
+    """src: [cout,cin,3,3] fp32 or bf16 tensor; packed: uint8 tensor of upconv_packed_bytes (for upsample2x_conv3x3)."""
+    cout, cin, _, _ = src.shape
+    _check(lib().wmdec_pack_upconv_weights(_ptr(src), dtype_enum(src), cout, cin, _ptr(packed), op_dtype, _stream()))
 
 
 def upsample2x_conv3x3(x, w_packed, bias, y):

@@ -41,6 +41,17 @@ def pack(w_oihw, dtype):
     return packed
 
 
+def pack_upconv(w_oihw, dtype):
+    """Pack [cout,cin,3,3] float32 weights of an upsampling convolution (9-tap pack + phase pack) through the ABI."""
+    cout, cin, _, _ = w_oihw.shape
+    src = torch.from_numpy(np.ascontiguousarray(w_oihw, dtype=np.float32)).cuda()
+    nbytes = wmdec.upconv_packed_bytes(cout, cin, ENUM[dtype])
+    assert nbytes > 0
+    packed = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    wmdec.pack_upconv_weights(src, packed, ENUM[dtype])
+    return packed
+
+
 def gn_stats(x_dev, groups, eps):
     n, h, w, c = x_dev.shape
     ws = torch.zeros(max(wmdec.gn_stats_workspace_bytes(n, h, w, c, groups), 256), dtype=torch.uint8, device="cuda")   # ticket counter starts at zero

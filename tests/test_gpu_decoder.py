@@ -75,7 +75,7 @@ def test_workload2_upsample_stage_reduced(dtype):
     p = resblock_params(synth.weight_seed(1) + 1, 256, 256, True)
     xd = G.dev_nhwc(x, dtype)
     u = torch.empty((1, 60, 88, 256), dtype=G.TORCH[dtype], device="cuda")
-    wmdec.upsample2x_conv3x3(xd, G.pack(wu, dtype), G.dev_f32(bu), u)
+    wmdec.upsample2x_conv3x3(xd, G.pack_upconv(wu, dtype), G.dev_f32(bu), u)
     y = resblock_gpu(u, p, dtype, 32, 1e-6, "f32")
     want = ref.resblock(ref.upconv(x, wu, bu), p, 32, 1e-6)
     err = ref.rel_err(G.host_nchw(y), want)

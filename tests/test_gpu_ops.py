@@ -185,27 +185,29 @@ def test_upsample2x_conv3x3(dtype, ydtype, n, cin, cout, h, w):
     x = G.stored(r.standard_normal((n, cin, h, w)), dtype)
     wt, b = synth.conv_params(r, cout, cin, 3, dtype != "f32")
     y, check = G.canaried((n, 2 * h, 2 * w, cout), G.TORCH[ydtype])
-    wmdec.upsample2x_conv3x3(G.dev_nhwc(x, dtype), G.pack(wt, dtype), G.dev_f32(b), y)
+    wmdec.upsample2x_conv3x3(G.dev_nhwc(x, dtype), G.pack_upconv(wt, dtype), G.dev_f32(b), y)
     torch.cuda.synchronize()
     check()
     want = ref.upconv(x, G.stored(wt, dtype) if dtype != "f32" else wt, b)
     assert ref.rel_err(G.host_nchw(y), want) <= G.TOL[dtype] / (2 if ydtype == "f32" else 1)
 
 
-def test_upconv_gather_index_map_bit_exact():
+# 32 channels: general kernel; 64: matrix-core kernel, 3x3 form (bf16) and phase-decomposed form (f16)
+@pytest.mark.parametrize("ch,dtype", [(32, "bf16"), (64, "bf16"), (64, "f16")])
+def test_upconv_gather_index_map_bit_exact(ch, dtype):
     """One-hot kernels turn the fused upsample-conv into a pure gather: the output must equal the
     shifted, zero-padded upsampled input bit for bit, for all nine taps."""
     r = rng(13)
-    x = G.stored(r.standard_normal((1, 32, 7, 10)), "bf16")
+    x = G.stored(r.standard_normal((1, ch, 7, 10)), dtype)
     up = np.pad(ref.upsample2x(x), ((0, 0), (0, 0), (1, 1), (1, 1)))
-    xd = G.dev_nhwc(x, "bf16")
+    xd = G.dev_nhwc(x, dtype)
     for ky in range(3):
         for kx in range(3):
-            w = np.zeros((32, 32, 3, 3), np.float32)
-            for c in range(32):
+            w = np.zeros((ch, ch, 3, 3), np.float32)
+            for c in range(ch):
                 w[c, c, ky, kx] = 1.0
-            y = torch.empty((1, 14, 20, 32), dtype=torch.bfloat16, device="cuda")
-            wmdec.upsample2x_conv3x3(xd, G.pack(w, "bf16"), None, y)
+            y = torch.empty((1, 14, 20, ch), dtype=G.TORCH[dtype], device="cuda")
+            wmdec.upsample2x_conv3x3(xd, G.pack_upconv(w, dtype), None, y)
             assert np.array_equal(G.host_nchw(y), up[:, :, ky:ky + 14, kx:kx + 20]), (ky, kx)
 
 
