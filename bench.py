@@ -18,6 +18,11 @@ sys.path.insert(0, ROOT)
 
 PEAK = {"mfma": 2516.6, "hbm": 8000.0}   # TFLOP/s dense bf16/f16 MFMA, GB/s HBM3E (published MI355X figures)
 
+# HBM traffic per launch (MB read, MB written) of the kernels that can dominate, averaged over their launches in one
+# frame: counter passes of this same command under rocprofv3, scaled by what the counters read for a plain copy of
+# known size.  Counters cannot be collected from inside this process; the passes are summarised under profiles/.
+PMC_TRAFFIC_MB = {}
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -72,33 +77,35 @@ def main():
     fps = args.batch * args.steps / elapsed
     assert bool(torch.isfinite(out).all())
 
-    # ---- roofline of the dominant kernel: the same steps again with HIP events around every graph step
+    # ---- roofline of the dominant kernel: every graph step again, `reps` launches back to back between two HIP
+    # events on the stream the kernels run on (the workspace still holds the tensors of the last run, and no step
+    # overwrites its own inputs), grouped by the kernel that executes the step
     info = dec.step_info()
-    dec.set_profiling(True)
-    acc = [0.0] * len(info)
-    for _ in range(args.steps):
-        dec.run(zd, packed, out)
-        for i, ms in enumerate(dec.step_times()):
-            acc[i] += ms
-    dec.set_profiling(False)
+    reps = 10
     fam = {}
-    for (kernel, flops, nbytes), ms in zip(info, acc):
+    for i, (kernel, flops, nbytes) in enumerate(info):
+        ms = dec.time_step(zd, packed, out, i, reps)
         f = fam.setdefault(kernel, {"ms": 0.0, "flops": 0.0, "bytes": 0.0, "launches": 0})
-        f["ms"] += ms / args.steps
+        f["ms"] += ms
         f["flops"] += flops * args.batch
         f["bytes"] += nbytes * args.batch
         f["launches"] += 1
     dom = max(fam, key=lambda k: fam[k]["ms"])
     d = fam[dom]
-    bound = "mfma" if dom.startswith("conv_mfma") or dom == "flash_attn" else "hbm"
+    bound = "mfma" if dom.startswith("conv_mfma") or dom.startswith("flash_attn") else "hbm"
     if bound == "mfma":
         achieved = d["flops"] / (d["ms"] * 1e-3) / 1e12
         unit = "TFLOP/s"
     else:
         achieved = d["bytes"] / (d["ms"] * 1e-3) / 1e9
         unit = "GB/s"
+    traffic = None
+    if args.batch == 1 and args.dtype == "f16" and dom in PMC_TRAFFIC_MB:
+        fetch_mb, write_mb = PMC_TRAFFIC_MB[dom]
+        traffic = {"fetch_mb_per_launch": fetch_mb, "write_mb_per_launch": write_mb,
+                   "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, copy-calibrated (profiles/)"}
     roofline = {"kernel": dom, "bound": bound, "achieved": round(achieved, 2), "peak": PEAK[bound], "unit": unit,
-                "frac": round(achieved / PEAK[bound], 4), "traffic": None,
+                "frac": round(achieved / PEAK[bound], 4), "traffic": traffic,
                 "launches_per_step": d["launches"], "avg_launch_us": round(d["ms"] * 1e3 / d["launches"], 2),
                 "algorithmic_gflop_per_launch": round(d["flops"] / d["launches"] / 1e9, 3),
                 "algorithmic_mb_per_launch": round(d["bytes"] / d["launches"] / 1e6, 3)}

@@ -33,8 +33,8 @@ int launch_conv(const ConvArgs& a, hipStream_t s) {
 }
 
 const char* conv_kernel_label(const ConvArgs& a) {
-  if (!conv_mfma_supported(a)) return "conv_direct";
-  return a.ksize == 3 ? "conv_mfma_3x3" : "conv_mfma_1x1";
+  if (!conv_mfma_supported(a)) return "conv_direct_kernel";
+  return conv_mfma_label(a);
 }
 
 static inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
@@ -662,34 +662,21 @@ int decoder_set_workspace(wmdec_decoder* dec, void* workspace, size_t bytes) {
   return WMDEC_OK;
 }
 
-int decoder_run(wmdec_decoder* dec, const void* latent, const void* packed, void* out, int batch, void* stream) {
-  WMDEC_REQUIRE(dec && latent && packed && out, WMDEC_ERR_INVALID_ARG, "decoder_run: null pointer");
-  WMDEC_REQUIRE(batch >= 1 && batch <= dec->cfg.max_batch, WMDEC_ERR_INVALID_ARG, "decoder_run: batch %d outside 1..%d", batch, dec->cfg.max_batch);
-  WMDEC_REQUIRE(aligned16(latent) && aligned16(packed) && aligned16(out), WMDEC_ERR_INVALID_ARG, "decoder_run: pointers must be 16-byte aligned");
-  const WsLayout L = ws_layout(dec, batch);
-  WMDEC_REQUIRE(dec->ws && dec->ws_bytes >= L.total, WMDEC_ERR_WORKSPACE, "decoder_run: workspace needs %zu bytes, has %zu", L.total, dec->ws_bytes);
-  hipStream_t s = (hipStream_t)stream;
+// enqueues one step of the plan; *emitted_slots carries the slot count of the last emitting convolution
+static int launch_step(wmdec_decoder* dec, const WsLayout& L, const Step& st, const void* latent, const void* packed,
+                       void* out, int batch, int* emitted_slots, hipStream_t s) {
   char* ws = (char*)dec->ws;
   const char* pk = (const char*)packed;
   const wmdec_decoder_config& c = dec->cfg;
   float* mean = (float*)(ws + L.mean);
   float* rstd = (float*)(ws + L.rstd);
   auto buf = [&](int id) -> void* { return id >= 0 ? (void*)(ws + L.act[id]) : nullptr; };
-  if (dec->ws_fresh) {   // once per workspace: the ticket counter of the statistics kernel starts at zero
-    const int rc0 = launch_zero_u32(ws + L.tickets, (int)(gn_stats_ticket_bytes(dec->cfg.max_batch) / 4), s);
-    if (rc0 != WMDEC_OK) return rc0;
-    dec->ws_fresh = false;
-  }
-  const bool prof = dec->profiling;
-  if (prof) { dec->profiled_batch = batch; WMDEC_HIP(hipEventRecord(dec->events[0], s)); }
-  size_t step_index = 0;
-  int emitted_slots = 0;   // moment slots per (sample, group) left by the last emitting convolution
-  for (const Step& st : dec->steps) {
+  {
     int rc = WMDEC_OK;
     switch (st.kind) {
       case Step::STATS:
-        if (st.from_producer && emitted_slots > 0)
-          rc = launch_gn_finalize(ws + L.stats_ws, batch * c.groups, emitted_slots, c.eps, mean, rstd, s);
+        if (st.from_producer && (*emitted_slots) > 0)
+          rc = launch_gn_finalize(ws + L.stats_ws, batch * c.groups, (*emitted_slots), c.eps, mean, rstd, s);
         else
           rc = launch_gn_stats(buf(st.src), c.act_dtype, batch, st.h, st.w, st.cin, c.groups, c.eps, mean, rstd,
                                (unsigned*)(ws + L.tickets), ws + L.stats_ws, L.stats_ws_bytes, s);
@@ -710,8 +697,8 @@ int decoder_run(wmdec_decoder* dec, const void* latent, const void* packed, void
         a.n = batch; a.h = st.h; a.w = st.w; a.cin = st.cin; a.cout = st.cout; a.ksize = st.ksize; a.upsample = st.upsample;
         if (st.emit_stats) {
           a.stats_groups = c.groups;
-          emitted_slots = conv_mfma_stats_slots(a);
-          if (emitted_slots > 0) a.stats_ws = ws + L.stats_ws;
+          (*emitted_slots) = conv_mfma_stats_slots(a);
+          if ((*emitted_slots) > 0) a.stats_ws = ws + L.stats_ws;
         }
         rc = launch_conv(a, s);
         break;
@@ -732,10 +719,68 @@ int decoder_run(wmdec_decoder* dec, const void* latent, const void* packed, void
         break;
       }
     }
+    return rc;
+  }
+}
+
+int decoder_run(wmdec_decoder* dec, const void* latent, const void* packed, void* out, int batch, void* stream) {
+  WMDEC_REQUIRE(dec && latent && packed && out, WMDEC_ERR_INVALID_ARG, "decoder_run: null pointer");
+  WMDEC_REQUIRE(batch >= 1 && batch <= dec->cfg.max_batch, WMDEC_ERR_INVALID_ARG, "decoder_run: batch %d outside 1..%d", batch, dec->cfg.max_batch);
+  WMDEC_REQUIRE(aligned16(latent) && aligned16(packed) && aligned16(out), WMDEC_ERR_INVALID_ARG, "decoder_run: pointers must be 16-byte aligned");
+  const WsLayout L = ws_layout(dec, batch);
+  WMDEC_REQUIRE(dec->ws && dec->ws_bytes >= L.total, WMDEC_ERR_WORKSPACE, "decoder_run: workspace needs %zu bytes, has %zu", L.total, dec->ws_bytes);
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)dec->ws;
+  if (dec->ws_fresh) {   // once per workspace: the ticket counter of the statistics kernel starts at zero
+    const int rc0 = launch_zero_u32(ws + L.tickets, (int)(gn_stats_ticket_bytes(dec->cfg.max_batch) / 4), s);
+    if (rc0 != WMDEC_OK) return rc0;
+    dec->ws_fresh = false;
+  }
+  const bool prof = dec->profiling;
+  if (prof) { dec->profiled_batch = batch; WMDEC_HIP(hipEventRecord(dec->events[0], s)); }
+  size_t step_index = 0;
+  int emitted_slots = 0;   // moment slots per (sample, group) left by the last emitting convolution
+  for (const Step& st : dec->steps) {
+    const int rc = launch_step(dec, L, st, latent, packed, out, batch, &emitted_slots, s);
     if (rc != WMDEC_OK) return rc;
     ++step_index;
     if (prof) WMDEC_HIP(hipEventRecord(dec->events[step_index], s));
   }
+  return WMDEC_OK;
+}
+
+int decoder_time_step(wmdec_decoder* dec, const void* latent, const void* packed, void* out, int batch, int step,
+                      int reps, float* ms_per_launch, void* stream) {
+  WMDEC_REQUIRE(dec && latent && packed && out && ms_per_launch, WMDEC_ERR_INVALID_ARG, "decoder_time_step: null pointer");
+  WMDEC_REQUIRE(batch >= 1 && batch <= dec->cfg.max_batch, WMDEC_ERR_INVALID_ARG, "decoder_time_step: batch %d outside 1..%d", batch, dec->cfg.max_batch);
+  WMDEC_REQUIRE(step >= 0 && step < (int)dec->steps.size() && reps >= 1, WMDEC_ERR_INVALID_ARG, "decoder_time_step: bad step or reps");
+  WMDEC_REQUIRE(!dec->ws_fresh, WMDEC_ERR_INVALID_ARG, "decoder_time_step: run decoder_run on this workspace first");
+  const WsLayout L = ws_layout(dec, batch);
+  WMDEC_REQUIRE(dec->ws && dec->ws_bytes >= L.total, WMDEC_ERR_WORKSPACE, "decoder_time_step: workspace needs %zu bytes, has %zu", L.total, dec->ws_bytes);
+  hipStream_t s = (hipStream_t)stream;
+  int emitted_slots = 0;   // what the emitting convolutions before this step left behind
+  for (int i = 0; i < step; ++i) {
+    const Step& st = dec->steps[i];
+    if (st.kind == Step::CONV && st.emit_stats) emitted_slots = conv_mfma_stats_slots(step_shape_args(*dec, st, batch));
+  }
+  hipEvent_t e0, e1;
+  WMDEC_HIP(hipEventCreate(&e0));
+  WMDEC_HIP(hipEventCreate(&e1));
+  int rc = WMDEC_OK;
+  hipError_t he = hipEventRecord(e0, s);
+  for (int r = 0; r < reps && rc == WMDEC_OK && he == hipSuccess; ++r) {
+    int slots = emitted_slots;
+    rc = launch_step(dec, L, dec->steps[step], latent, packed, out, batch, &slots, s);
+  }
+  if (he == hipSuccess) he = hipEventRecord(e1, s);
+  if (he == hipSuccess) he = hipEventSynchronize(e1);
+  float ms = 0.f;
+  if (he == hipSuccess) he = hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (rc != WMDEC_OK) return rc;
+  if (he != hipSuccess) return hip_fail(he, "decoder_time_step events");
+  *ms_per_launch = ms / (float)reps;
   return WMDEC_OK;
 }
 
@@ -762,15 +807,16 @@ int decoder_step_info(const wmdec_decoder* dec, int index, const char** kernel, 
   if (bytes) *bytes = st.bytes;
   if (kernel) {
     switch (st.kind) {
-      case Step::STATS: *kernel = st.from_producer ? "gn_finalize" : "gn_stats"; break;
-      case Step::QKV_TRANSPOSE_V: *kernel = "transpose"; break;
-      case Step::FLASH: *kernel = "flash_attn"; break;
+      case Step::STATS: *kernel = st.from_producer ? "gn_finalize" : "gn_stats_vec"; break;
+      case Step::QKV_TRANSPOSE_V: *kernel = "transpose_kernel"; break;
+      case Step::FLASH: *kernel = "flash_attn_kernel"; break;
       case Step::CONV: {
         ConvArgs a;   // only the fields the kernel choice looks at
         a.op_dtype = dec->cfg.act_dtype; a.res_dtype = a.op_dtype;
         a.x_dtype = st.src == BUF_LATENT ? (int)WMDEC_BF16 : a.op_dtype; a.x_nchw = st.x_nchw;
         a.y_dtype = st.dst == BUF_OUT ? (int)WMDEC_F32 : a.op_dtype; a.y_nchw = st.y_nchw;
         a.n = 1; a.h = st.h; a.w = st.w; a.cin = st.cin; a.cout = st.cout; a.ksize = st.ksize; a.upsample = st.upsample;
+        a.groups_norm = st.norm; a.silu = st.silu;
         *kernel = conv_kernel_label(a);
         break;
       }

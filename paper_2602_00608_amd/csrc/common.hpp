@@ -74,6 +74,7 @@ struct ConvArgs {
   const float* gamma = nullptr;  // [cin]
   const float* beta = nullptr;
   int groups = 1;
+  int groups_norm = 0;           // label queries only: the launch will normalise although mean is not known yet
   int silu = 0;
   const void* wt = nullptr;      // packed [k*k][cout][cin] in op dtype
   const void* wt_phase = nullptr;  // upsample only: the 16-tap phase pack (pre-summed 2x2 weights of the four output phases)
@@ -100,6 +101,7 @@ bool conv_mfma_supported(const ConvArgs& a);
 int launch_conv_mfma(const ConvArgs& a, hipStream_t s);
 // moment slots per (sample, group) the MFMA kernel would write for this launch; 0: it cannot emit statistics
 int conv_mfma_stats_slots(const ConvArgs& a);
+const char* conv_mfma_label(const ConvArgs& a);   // instantiation name, valid until the thread's next call
 // picks the kernel
 int launch_conv(const ConvArgs& a, hipStream_t s);
 const char* conv_kernel_label(const ConvArgs& a);

@@ -17,6 +17,7 @@
 // buffer after it, with one workgroup barrier per chunk.  Two workgroups fit on
 // a compute unit (registers <= 256, LDS < 80 KiB), so one activates while the
 // other multiplies.
+#include <stdio.h>
 #include <stdlib.h>
 
 #include <type_traits>
@@ -240,29 +241,20 @@ __device__ __forceinline__ void mfma_chunk(const T* buf, const int (&a_off)[MI],
       constexpr int sp = s + D - 1;
       const u32x4* src = sp < STEPS ? bcur : bnext;
       constexpr int spp = sp < STEPS ? sp : sp - STEPS;
-#ifndef WMDEC_ABL_NOB
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni)
         bq[sp % D][ni] = (src + ((spp / KK) * tap_stride + (spp % KK) * kk_stride + ni * 64))[lane];
-#endif
     }
     __builtin_amdgcn_sched_barrier(0);
     auto tile = [&](auto mi_c) {
       constexpr int mi = decltype(mi_c)::value;
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = Mma<T>::m32(af[mi], bq[s % D][ni], acc[mi][ni]);
-#ifndef WMDEC_ABL_NOA
-      if constexpr (s + 1 < STEPS)
-#else
-      if constexpr (false)
-#endif
-      {
+      if constexpr (s + 1 < STEPS) {
         constexpr int tap = (s + 1) / KK, kk = (s + 1) % KK;
         af[mi] = *reinterpret_cast<const u32x4*>(buf + a_off[mi] + ((tap / KS) * HW_ + tap % KS) * PS + kk * 16);
       }
-#ifndef WMDEC_ABL_NOSLICE
       if constexpr (SLICED) slice(std::integral_constant<int, s * MI + mi>{});
-#endif
       __builtin_amdgcn_sched_barrier(0);
     };
     static_for<MI>(tile);
@@ -383,9 +375,6 @@ __global__ __launch_bounds__(256, wave_m_tiles(TH, TW, WM, PH) * NI <= 4 ? 3 : 2
   // afterwards): a load under a lane mask makes the compiler wait for it at the end of the branch.
   u32x4 raw[NV];
   auto issue = [&](int chunk) {
-#ifdef WMDEC_ABL_NOISSUE
-    if (chunk > 1) return;
-#endif
     const int cb = min(chunk, p.cin / KC - 1) * KC * (int)sizeof(T);   // past the last chunk: a harmless reload
 #pragma unroll
     for (int i = 0; i < NV; ++i) raw[i] = *reinterpret_cast<const u32x4*>(xin + (unsigned)(max(src_off[i], 0) + cb));
@@ -425,13 +414,8 @@ __global__ __launch_bounds__(256, wave_m_tiles(TH, TW, WM, PH) * NI <= 4 ? 3 : 2
   TRACE(1);
   for (int c = 0; c < nchunks; ++c) {
     const bool more = c + 1 < nchunks;
-#ifdef WMDEC_ABL_SAMEB
-    const u32x4* bcur = wcol;
-    const u32x4* bnext = wcol + (more ? 0 : 0);
-#else
     const u32x4* bcur = wcol + (size_t)(c * KK) * kk_stride;
     const u32x4* bnext = more ? bcur + (size_t)KK * kk_stride : bcur;
-#endif
     const T* buf = s_a + (c & 1) * BUF;
     T* nbuf = s_a + ((c + 1) & 1) * BUF;
     const int c0n = (c + 1) * KC;
@@ -472,10 +456,6 @@ __global__ __launch_bounds__(256, wave_m_tiles(TH, TW, WM, PH) * NI <= 4 ? 3 : 2
   float* patch = reinterpret_cast<float*>(smem) + wave * patch_floats(NI);
   // statistics slot of this wavefront: [sample][group][spatial tile * WM + wave row]
   Moments* st = p.stats ? p.stats + (size_t)n * p.stats_groups * p.stats_slots + (tile * WM + wm) : nullptr;
-#ifdef WMDEC_ABL_NOEPI
-  if (acc[0][0][0] == 123.456f) yout[tid] = from_float<TO>(acc[1][1][3] + acc[2][0][5] + acc[3][1][7]);
-  else if (p.n < 0)
-#endif
   if (rin)
     epilogue_store<T, TO, MI, NI, MTW, MTH, MT_PER_ROW, true>(acc, patch, lane, PH ? 0 : wm * MI, ty0, tx0, co0 + wn * NI * 32, p.bias,
                                                               rin, yout, p.h, p.w_out, p.cout, false, st, p.stats_cpg, p.stats_slots,
@@ -626,6 +606,26 @@ int conv_mfma_stats_slots(const ConvArgs& a) {
   const TileShape& ts = kTiles[t];
   const int w_t = t == 9 ? a.w / 2 : a.w, h_t = t == 9 ? a.h / 2 : a.h;
   return ((w_t + ts.tw - 1) / ts.tw) * ((h_t + ts.th - 1) / ts.th) * ts.wm;
+}
+
+// the instantiation a launch would use, spelled like a profiler prints it
+const char* conv_mfma_label(const ConvArgs& a) {
+  static thread_local char buf[160];
+  read_env_once();
+  int t = pick_tile(a), kc = 32;
+  if (a.ksize == 1) {
+    if (a.cin % 64 == 0) kc = 64;
+    else if (t == 0) t = 1;
+    if (t != 0 && t != 1) t = 2;
+  } else if (t != 0 && t != 4 && t != 6 && t != 8 && t != 9) {
+    t = 7;
+  }
+  const TileShape& ts = kTiles[t];
+  const char* ty = a.op_dtype == WMDEC_BF16 ? "wmdec::bf16_t" : "wmdec::f16_t";
+  const int act = a.mean == nullptr && !a.groups_norm ? 0 : (a.silu ? 2 : 1);
+  snprintf(buf, sizeof(buf), "conv_mfma_kernel<%s, %s, %d, %d, %d, %d, %d, %d, %d, %d, %s>", ty,
+           a.y_dtype == WMDEC_F32 ? "float" : ty, ts.th, ts.tw, ts.wm, ts.wn, ts.ni, a.ksize, kc, act, t == 9 ? "true" : "false");
+  return buf;
 }
 
 int launch_conv_mfma(const ConvArgs& a, hipStream_t s) {

@@ -180,30 +180,34 @@ __global__ __launch_bounds__(256) void gn_partial_any(const T* __restrict__ x, i
   if (tid == 0) ws[((size_t)n * groups + g) * chunks + chunk] = s_m[0];
 }
 
-// grid = n*groups workgroups of 256 threads: thread t merges slots t, t+256, ... in order (loaded eight at a time,
-// so that a row costs one memory round trip), then a fixed butterfly over each wavefront, then wavefronts 0..3 in order.
-__global__ __launch_bounds__(256) void gn_finalize(const Moments* __restrict__ ws, int chunks, float eps,
-                                                   float* __restrict__ mean, float* __restrict__ rstd) {
-  __shared__ Moments s_w[4];
+// grid = n*groups workgroups of 1024 threads: thread t merges slots t, t+1024, ... in order (loaded four at a
+// time: a row of up to 4096 slots costs one memory round trip), then a fixed butterfly over each wavefront, then
+// the 16 wavefronts in order.
+constexpr int kFinThreads = 1024;
+__global__ __launch_bounds__(kFinThreads) void gn_finalize(const Moments* __restrict__ ws, int chunks, float eps,
+                                                           float* __restrict__ mean, float* __restrict__ rstd) {
+  __shared__ Moments s_w[kFinThreads / 64];
   const int ng = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
   const Moments* row = ws + (size_t)ng * chunks;
   Moments m{0.f, 0.f, 0.f};
-  for (int i0 = tid; i0 < chunks; i0 += 256 * 8) {
-    Moments t[8];
+  for (int i0 = tid; i0 < chunks; i0 += kFinThreads * 4) {
+    Moments t[4];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const int i = i0 + 256 * k;
+    for (int k = 0; k < 4; ++k) {
+      const int i = i0 + kFinThreads * k;
       t[k] = row[min(i, chunks - 1)];
       if (i >= chunks) t[k].n = 0.f;
     }
 #pragma unroll
-    for (int k = 0; k < 8; ++k) m = merge(m, t[k]);
+    for (int k = 0; k < 4; ++k) m = merge(m, t[k]);
   }
   for (int mask = 1; mask < 64; mask <<= 1) m = butterfly(m, lane, mask);   // lane-independent order
   if (lane == 0) s_w[tid >> 6] = m;
   __syncthreads();
   if (tid == 0) {
-    m = merge(merge(s_w[0], s_w[1]), merge(s_w[2], s_w[3]));
+    m = s_w[0];
+#pragma unroll
+    for (int k = 1; k < kFinThreads / 64; ++k) m = merge(m, s_w[k]);
     mean[ng] = m.mean;
     rstd[ng] = 1.0f / sqrtf(m.m2 / m.n + eps);
   }
@@ -245,7 +249,7 @@ Plan make_plan(int x_dtype, int n, int h, int w, int c, int groups) {
 }  // namespace
 
 int launch_gn_finalize(const void* ws, int n_groups, int slots, float eps, float* mean, float* rstd, hipStream_t s) {
-  hipLaunchKernelGGL(gn_finalize, dim3((unsigned)n_groups), dim3(256), 0, s, (const Moments*)ws, slots, eps, mean, rstd);
+  hipLaunchKernelGGL(gn_finalize, dim3((unsigned)n_groups), dim3(kFinThreads), 0, s, (const Moments*)ws, slots, eps, mean, rstd);
   WMDEC_HIP(hipGetLastError());
   return WMDEC_OK;
 }
@@ -283,7 +287,7 @@ int launch_gn_stats(const void* x, int x_dtype, int n, int h, int w, int c, int 
     }
   }
   WMDEC_HIP(hipGetLastError());
-  hipLaunchKernelGGL(gn_finalize, dim3((unsigned)(n * groups)), dim3(256), 0, s, wsm, p.chunks, eps, mean, rstd);
+  hipLaunchKernelGGL(gn_finalize, dim3((unsigned)(n * groups)), dim3(kFinThreads), 0, s, wsm, p.chunks, eps, mean, rstd);
   WMDEC_HIP(hipGetLastError());
   return WMDEC_OK;
 }

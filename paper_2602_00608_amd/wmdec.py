@@ -71,6 +71,7 @@ SIGNATURES = {
     "decoder_step_info": (_i, [_vp, _i, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_double),
                                ctypes.POINTER(ctypes.c_double)]),
     "decoder_step_times": (_i, [_vp, ctypes.POINTER(ctypes.c_float), _i]),
+    "decoder_time_step": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, ctypes.POINTER(ctypes.c_float), _vp]),
 }
 
 _lib = None
@@ -280,6 +281,13 @@ class Decoder:
         ms = (ctypes.c_float * n)()
         _check(lib().decoder_step_times(self.handle, ms, n))
         return list(ms)
+
+    def time_step(self, latent, packed, out, step, reps):
+        """Mean milliseconds per launch of graph step `step`, `reps` launches back to back (after a run())."""
+        ms = ctypes.c_float()
+        _check(lib().decoder_time_step(self.handle, _ptr(latent), _ptr(packed), _ptr(out), latent.shape[0], step, reps,
+                                       ctypes.byref(ms), _stream()))
+        return ms.value
 
     def run(self, latent, packed, out):
         _check(lib().decoder_run(self.handle, _ptr(latent), _ptr(packed), _ptr(out), latent.shape[0], _stream()))
