@@ -21,7 +21,13 @@ PEAK = {"mfma": 2516.6, "hbm": 8000.0}   # TFLOP/s dense bf16/f16 MFMA, GB/s HBM
 # HBM traffic per launch (MB read, MB written) of the kernels that can dominate, averaged over their launches in one
 # frame: counter passes of this same command under rocprofv3, scaled by what the counters read for a plain copy of
 # known size.  Counters cannot be collected from inside this process; the passes are summarised under profiles/.
-PMC_TRAFFIC_MB = {}
+PMC_TRAFFIC_MB = {
+    "conv_mfma_kernel<wmdec::f16_t, wmdec::f16_t, 8, 16, 2, 2, 2, 3, 32, 2, false>": (88.9, 20.8),
+    "conv_mfma_kernel<wmdec::f16_t, wmdec::f16_t, 8, 32, 2, 2, 2, 3, 32, 2, false>": (179.2, 89.6),
+    "conv_mfma_kernel<wmdec::f16_t, wmdec::f16_t, 8, 16, 4, 1, 2, 3, 32, 0, true>": (168.0, 96.3),
+    "conv_mfma_kernel<wmdec::f16_t, wmdec::f16_t, 8, 32, 2, 2, 2, 1, 64, 0, false>": (179.1, 66.4),
+    "flash_attn_kernel": (136.4, 75.1),
+}
 
 
 def main():
@@ -33,6 +39,8 @@ def main():
     ap.add_argument("--dtype", default="f16", choices=["f16", "bf16"],
                     help="storage / MFMA operand type of activations (weights and latents are given in bf16)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="first copy 256 MiB device to device three times: a kernel of known traffic for counter passes")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (frames shard over GPUs with no exchange; "
@@ -46,6 +54,14 @@ def main():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     torch.cuda.set_device(0)
     stream = torch.cuda.current_stream()
+
+    if args.calibration_copy:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     cfg = wmdec.decoder_default_config()
     cfg.act_dtype = wmdec.F16 if args.dtype == "f16" else wmdec.BF16
@@ -99,13 +115,14 @@ def main():
     else:
         achieved = d["bytes"] / (d["ms"] * 1e-3) / 1e9
         unit = "GB/s"
-    traffic = None
+    traffic = traffic_detail = None   # HBM bytes per launch
     if args.batch == 1 and args.dtype == "f16" and dom in PMC_TRAFFIC_MB:
         fetch_mb, write_mb = PMC_TRAFFIC_MB[dom]
-        traffic = {"fetch_mb_per_launch": fetch_mb, "write_mb_per_launch": write_mb,
-                   "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, copy-calibrated (profiles/)"}
+        traffic = round((fetch_mb + write_mb) * 1e6)
+        traffic_detail = {"fetch_mb_per_launch": fetch_mb, "write_mb_per_launch": write_mb,
+                          "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes of this command, copy-calibrated (profiles/)"}
     roofline = {"kernel": dom, "bound": bound, "achieved": round(achieved, 2), "peak": PEAK[bound], "unit": unit,
-                "frac": round(achieved / PEAK[bound], 4), "traffic": traffic,
+                "frac": round(achieved / PEAK[bound], 4), "traffic": traffic, "traffic_detail": traffic_detail,
                 "launches_per_step": d["launches"], "avg_launch_us": round(d["ms"] * 1e3 / d["launches"], 2),
                 "algorithmic_gflop_per_launch": round(d["flops"] / d["launches"] / 1e9, 3),
                 "algorithmic_mb_per_launch": round(d["bytes"] / d["launches"] / 1e6, 3)}
