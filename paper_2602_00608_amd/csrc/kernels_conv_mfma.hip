@@ -270,8 +270,10 @@ __device__ __forceinline__ void mfma_chunk(const T* buf, const int (&a_off)[MI],
 constexpr int wave_m_tiles(int th, int tw, int wm, bool ph) { return ph ? th * tw / 32 : th * tw / 32 / wm; }
 
 template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC, int ACT, bool PH = false>
-__global__ __launch_bounds__(256, wave_m_tiles(TH, TW, WM, PH) * NI <= 4 ? 3 : 2) void conv_mfma_kernel(MfmaParams p) {
-  static_assert(WM * WN == 4, "four wavefronts");
+__global__ __launch_bounds__(64 * WM * WN, WM * WN == 8 ? 1 : (wave_m_tiles(TH, TW, WM, PH) * NI <= 4 ? 3 : 2))
+void conv_mfma_kernel(MfmaParams p) {
+  static_assert(WM * WN == 4 || WM * WN == 8, "four or eight wavefronts");
+  constexpr int NT = 64 * WM * WN;               // threads of the workgroup
   static_assert(!PH || (KS == 3 && WM == 4 && WN == 1), "phase mode: one wavefront per phase");
   constexpr int MI = wave_m_tiles(TH, TW, WM, PH);   // 32-pixel M tiles per wavefront
   constexpr int KT = PH ? 2 : KS;                // taps per dimension a wavefront sweeps
@@ -281,11 +283,11 @@ __global__ __launch_bounds__(256, wave_m_tiles(TH, TW, WM, PH) * NI <= 4 ? 3 : 2
   constexpr int MTW = TW < 32 ? TW : 32, MTH = 32 / MTW, MT_PER_ROW = TW / MTW;
   constexpr int TN = WN * NI * 32;
   constexpr int VPP = KC / 8;                    // 16-byte vectors per pixel per chunk
-  constexpr int NV = (HP * VPP + 255) / 256;     // vectors a thread stages per chunk
-  constexpr int BUF = (NV * 256 / VPP) * PS;     // elements of one staged tile (rounded up: every thread stores all its NV vectors)
+  constexpr int NV = (HP * VPP + NT - 1) / NT;   // vectors a thread stages per chunk
+  constexpr int BUF = (NV * NT / VPP) * PS;      // elements of one staged tile (rounded up: every thread stores all its NV vectors)
   constexpr int STEPS = KT * KT * (KC / 16), SLOTS = STEPS * MI;
   constexpr bool SLICED = KS == 3;               // activation of the next chunk is sliced into the MFMA sweep
-  static_assert(256 % VPP == 0, "a thread keeps one channel octet");
+  static_assert(NT % VPP == 0, "a thread keeps one channel octet");
 
   extern __shared__ __align__(16) unsigned char smem[];
   T* s_a = reinterpret_cast<T*>(smem);                                          // [2][HP][PS]
@@ -315,7 +317,7 @@ __global__ __launch_bounds__(256, wave_m_tiles(TH, TW, WM, PH) * NI <= 4 ? 3 : 2
   // per-channel scale/shift table: a = gamma*rstd, b = beta - mean*a
   if constexpr (ACT > 0) {
     const int cpg = p.cin / p.groups;
-    for (int c = tid; c < p.cin; c += 256) {
+    for (int c = tid; c < p.cin; c += NT) {
       const int g = c / cpg;
       const float a = p.gamma[c] * p.rstd[n * p.groups + g];
       s_ab[c] = make_float2(a, p.beta[c] - p.mean[n * p.groups + g] * a);
@@ -356,7 +358,7 @@ __global__ __launch_bounds__(256, wave_m_tiles(TH, TW, WM, PH) * NI <= 4 ? 3 : 2
   int src_off[NV];          // byte offset of the vector in x (chunk 0), or -1: outside the image / past the tile
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
-    const int v = tid + i * 256;
+    const int v = tid + i * NT;
     const int hp = v / VPP;
     const int hy = hp / HW_, hx = hp % HW_;
     const int gy = ty0 + hy - PAD, gx = tx0 + hx - PAD;
@@ -390,7 +392,7 @@ __global__ __launch_bounds__(256, wave_m_tiles(TH, TW, WM, PH) * NI <= 4 ? 3 : 2
     return src_off[i] >= 0 ? wv : 0u;   // zero padding acts on the activated tensor
   };
   auto store_vec = [&](int i, T* buf) {
-    *reinterpret_cast<u32x4*>(buf + ((tid + i * 256) / VPP) * PS + cvec * 8) = raw[i];
+    *reinterpret_cast<u32x4*>(buf + ((tid + i * NT) / VPP) * PS + cvec * 8) = raw[i];
   };
   auto activate_all = [&](int c0, T* buf) {
 #pragma unroll
@@ -490,9 +492,10 @@ int launch_cfg(const ConvArgs& a, hipStream_t s) {
 #ifdef WMDEC_TRACE
   p.trace = g_trace;
 #endif
-  constexpr int NV = (HP * (KC / 8) + 255) / 256;
-  size_t smem = (((size_t)2 * (NV * 256 / (KC / 8)) * (KC + 8) * 2 + 15) & ~(size_t)15) + (size_t)a.cin * sizeof(float2);
-  const size_t patch = (size_t)4 * patch_floats(NI) * sizeof(float);   // epilogue patches of the four wavefronts
+  constexpr int NT = 64 * WM * WN;
+  constexpr int NV = (HP * (KC / 8) + NT - 1) / NT;
+  size_t smem = (((size_t)2 * (NV * NT / (KC / 8)) * (KC + 8) * 2 + 15) & ~(size_t)15) + (size_t)a.cin * sizeof(float2);
+  const size_t patch = (size_t)(WM * WN) * patch_floats(NI) * sizeof(float);   // epilogue patches of the wavefronts
   if (smem < patch) smem = patch;
   WMDEC_REQUIRE(smem <= 80 * 1024, WMDEC_ERR_UNSUPPORTED, "conv_mfma: %zu bytes of LDS needed", smem);
   void (*kern)(MfmaParams) = !p.norm ? conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 0, PH>
@@ -504,7 +507,7 @@ int launch_cfg(const ConvArgs& a, hipStream_t s) {
     WMDEC_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024));   // two workgroups per compute unit
     attr_set[mode] = true;
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)p.total), dim3(256), smem, s, p);
+  hipLaunchKernelGGL(kern, dim3((unsigned)p.total), dim3(NT), smem, s, p);
   WMDEC_HIP(hipGetLastError());
   return WMDEC_OK;
 }
@@ -522,6 +525,10 @@ constexpr TileShape kTiles[] = {
     {8, 32, 4, 1, 1},    // 7: 256 x 32 (few output channels: the frame)
     {8, 32, 1, 4, 1},    // 8: 256 x 128, every wavefront all pixels x 32 channels: no weight fragment is loaded twice
     {8, 16, 4, 1, 2},    // 9: phase-decomposed upsampling convolution: 8x16 input pixels (16x32 outputs) x 64 channels
+    {8, 16, 2, 4, 1},    // 10: 128 x 128 with eight wavefronts (64 pixels x 32 channels each): small layers that leave
+                         //     compute units empty run two wavefronts per SIMD, so vector-ALU work hides under another's MFMAs
+    {8, 16, 1, 4, 1},    // 11: 128 x 128, every wavefront all pixels x 32 channels: a weight fragment feeds four MFMAs
+                         //     (two in shape 4), which halves the load on the vector L1 (64 B/clk per compute unit)
 };
 
 // which tile shape a launch uses (3x3: any of the above; 1x1: 0, 1 or 2)
@@ -533,7 +540,7 @@ int pick_tile(const ConvArgs& a) {
     // that type a visible part of its error budget
     if (a.upsample && a.op_dtype == WMDEC_F16 && a.cout % 64 == 0 && g_tile != 0) return 9;
     if (a.cout <= 32) return 7;
-    int t = (g_tile == 0 || g_tile == 4 || g_tile == 6 || g_tile == 8) ? g_tile : ((n128 && px * (a.cout / 128) >= 256L * 256 * 3) ? 0 : (n128 ? 4 : 6));
+    int t = (g_tile == 0 || g_tile == 4 || g_tile == 6 || g_tile == 8 || g_tile == 10 || g_tile == 11) ? g_tile : ((n128 && px * (a.cout / 128) >= 256L * 256 * 3) ? 0 : (n128 ? 4 : 6));
     if (!n128) t = 6;
     return t;
   }
@@ -549,6 +556,8 @@ int launch_3x3(const ConvArgs& a, hipStream_t s) {
     case 6: return launch_cfg<T, TO, 8, 16, 4, 1, 2, 3, 32>(a, s);
     case 8: return launch_cfg<T, TO, 8, 32, 1, 4, 1, 3, 32>(a, s);
     case 9: return launch_cfg<T, TO, 8, 16, 4, 1, 2, 3, 32, true>(a, s);
+    case 10: return launch_cfg<T, TO, 8, 16, 2, 4, 1, 3, 32>(a, s);
+    case 11: return launch_cfg<T, TO, 8, 16, 1, 4, 1, 3, 32>(a, s);
     default: return launch_cfg<T, TO, 8, 32, 4, 1, 1, 3, 32>(a, s);
   }
 }
@@ -617,7 +626,7 @@ const char* conv_mfma_label(const ConvArgs& a) {
     if (a.cin % 64 == 0) kc = 64;
     else if (t == 0) t = 1;
     if (t != 0 && t != 1) t = 2;
-  } else if (t != 0 && t != 4 && t != 6 && t != 8 && t != 9) {
+  } else if (t != 0 && t != 4 && t != 6 && t != 8 && t != 9 && t != 10 && t != 11) {
     t = 7;
   }
   const TileShape& ts = kTiles[t];
