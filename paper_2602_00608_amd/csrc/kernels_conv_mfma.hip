@@ -540,7 +540,11 @@ int pick_tile(const ConvArgs& a) {
     // that type a visible part of its error budget
     if (a.upsample && a.op_dtype == WMDEC_F16 && a.cout % 64 == 0 && g_tile != 0) return 9;
     if (a.cout <= 32) return 7;
-    int t = (g_tile == 0 || g_tile == 4 || g_tile == 6 || g_tile == 8 || g_tile == 10 || g_tile == 11) ? g_tile : ((n128 && px * (a.cout / 128) >= 256L * 256 * 3) ? 0 : (n128 ? 4 : 6));
+    // 256-pixel tiles when that still gives three per compute unit; else 128-pixel tiles, with one weight
+    // fragment per four MFMAs (shape 11) unless the layer leaves compute units empty anyway (shape 4)
+    const long work = px * (a.cout / 128);
+    int t = (g_tile == 0 || g_tile == 4 || g_tile == 6 || g_tile == 8 || g_tile == 10 || g_tile == 11) ? g_tile
+            : (n128 && work >= 256L * 256 * 3) ? 0 : (n128 ? (work >= 128L * 256 * 2 ? 11 : 4) : 6);
     if (!n128) t = 6;
     return t;
   }
