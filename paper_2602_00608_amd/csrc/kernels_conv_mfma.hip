@@ -45,6 +45,7 @@ struct MfmaParams {
   int n, h, w_out, cin, cout, upsample;
   int tiles_x, tiles_y, ntiles, total;
   int cin_blocks, cout_blocks;   // packed-layout extents: ceil(cin/16), ceil(cout/32)
+  int w_bytes;                   // size of the packed weights the kernel may read
   int y_nchw;                    // 1: y is planar [n][cout][h][w] (the frame), else NHWC
   Moments* stats;                // non-null: moments of y per (sample, group, slot); slot = spatial tile * WM + wave row
   int stats_cpg, stats_groups, stats_slots;
@@ -218,6 +219,13 @@ constexpr int prefetch_ring(int steps, int room) {
   return steps % 3 == 0 ? 3 : (steps % 4 == 0 ? 4 : 2);
 }
 
+// One weight fragment (1 KiB, a lane's 16 bytes at lane16 = 16 * lane) at byte offset `off` of the packed weights.
+// A buffer load takes the wave-uniform offset in a scalar register, so the address costs no vector-ALU work
+// (a global load would add the 64-bit base per fragment), and offsets past the blob read zeros instead of faulting.
+__device__ __forceinline__ u32x4 load_fragment(__amdgpu_buffer_rsrc_t rsrc, int lane16, int off) {
+  return __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane16, off, 0);
+}
+
 // MFMA work of one staged chunk: STEPS = taps * KC/16 k-steps, each MI x NI 32x32x16 MFMAs.
 // Weight fragments are fetched D-1 steps ahead (bq is a ring that persists across chunks: on
 // entry it holds steps 0..D-2 of this chunk, on exit steps 0..D-2 of the chunk at `bnext`).
@@ -226,8 +234,8 @@ constexpr int prefetch_ring(int steps, int room) {
 // barriers pin that order: without them the compiler sinks every load to just before its use
 // and each k-step pays a full memory latency.
 template <typename T, int MI, int NI, int KS, int KC, int HW_, int PS, int D, bool SLICED, typename Slice>
-__device__ __forceinline__ void mfma_chunk(const T* buf, const int (&a_off)[MI], const u32x4* bcur, const u32x4* bnext,
-                                           int tap_stride, int kk_stride, int lane, u32x4 (&bq)[D][NI],
+__device__ __forceinline__ void mfma_chunk(const T* buf, const int (&a_off)[MI], __amdgpu_buffer_rsrc_t wrsrc, int bcur, int bnext,
+                                           int tap_stride, int kk_stride, int lane16, u32x4 (&bq)[D][NI],
                                            f32x16 (&acc)[MI][NI], Slice&& slice) {
   constexpr int KK = KC / 16, STEPS = KS * KS * KK;
   u32x4 af[MI];
@@ -239,11 +247,11 @@ __device__ __forceinline__ void mfma_chunk(const T* buf, const int (&a_off)[MI],
     constexpr int s = decltype(s_c)::value;
     {
       constexpr int sp = s + D - 1;
-      const u32x4* src = sp < STEPS ? bcur : bnext;
+      const int src = sp < STEPS ? bcur : bnext;
       constexpr int spp = sp < STEPS ? sp : sp - STEPS;
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni)
-        bq[sp % D][ni] = (src + ((spp / KK) * tap_stride + (spp % KK) * kk_stride + ni * 64))[lane];
+        bq[sp % D][ni] = load_fragment(wrsrc, lane16, src + (spp / KK) * tap_stride + (spp % KK) * kk_stride + ni * 1024);
     }
     __builtin_amdgcn_sched_barrier(0);
     auto tile = [&](auto mi_c) {
@@ -269,8 +277,14 @@ __device__ __forceinline__ void mfma_chunk(const T* buf, const int (&a_off)[MI],
 // weights (taps 4 * w .. 4 * w + 3 of the 16-tap phase pack): 4/9 of the multiplications of the 3x3 form.
 constexpr int wave_m_tiles(int th, int tw, int wm, bool ph) { return ph ? th * tw / 32 : th * tw / 32 / wm; }
 
-template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC, int ACT, bool PH = false>
-__global__ __launch_bounds__(64 * WM * WN, WM * WN == 8 ? 1 : (wave_m_tiles(TH, TW, WM, PH) * NI <= 4 ? 3 : 2))
+// Pixel slots of a staged tile: every thread stores all its NV vectors, and at least one slot behind the patch is
+// spare: vectors that lie outside the image (or past the patch) are stored there, where no MFMA reads them.
+constexpr int tile_pixel_slots(int stored, int hp) { return stored > hp ? stored : hp + 1; }
+
+// RING: length of the weight prefetch ring (0: the default for the tile); a long ring is for layers with too few
+// workgroups to keep more than one wavefront per SIMD busy, where a k-step is short against the L2 latency
+template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC, int ACT, bool PH = false, int RING = 0>
+__global__ __launch_bounds__(64 * WM * WN, WM * WN == 8 ? 1 : ((wave_m_tiles(TH, TW, WM, PH) * NI <= 4 && RING == 0) ? 3 : 2))
 void conv_mfma_kernel(MfmaParams p) {
   static_assert(WM * WN == 4 || WM * WN == 8, "four or eight wavefronts");
   constexpr int NT = 64 * WM * WN;               // threads of the workgroup
@@ -284,7 +298,7 @@ void conv_mfma_kernel(MfmaParams p) {
   constexpr int TN = WN * NI * 32;
   constexpr int VPP = KC / 8;                    // 16-byte vectors per pixel per chunk
   constexpr int NV = (HP * VPP + NT - 1) / NT;   // vectors a thread stages per chunk
-  constexpr int BUF = (NV * NT / VPP) * PS;      // elements of one staged tile (rounded up: every thread stores all its NV vectors)
+  constexpr int BUF = tile_pixel_slots(NV * NT / VPP, HP) * PS;   // elements of one staged tile: the halo patch plus spare pixel slots
   constexpr int STEPS = KT * KT * (KC / 16), SLOTS = STEPS * MI;
   constexpr bool SLICED = KS == 3;               // activation of the next chunk is sliced into the MFMA sweep
   static_assert(NT % VPP == 0, "a thread keeps one channel octet");
@@ -341,31 +355,46 @@ void conv_mfma_kernel(MfmaParams p) {
     a_off[mi] = (ty * HW_ + tx) * PS + 8 * lk + (PH ? ((wave >> 1) * HW_ + (wave & 1)) * PS : 0);
   }
   constexpr int KK = KC / 16;
-  constexpr int D = prefetch_ring(KT * KT * KK, MI * NI);   // weight fragments are fetched D-1 k-steps ahead
-  const int tap_stride = p.cin_blocks * p.cout_blocks * 64, kk_stride = p.cout_blocks * 64;   // in 16-byte units
-  // fragment column of this wavefront (uniform pointer; the lane index is added at the load)
-  const u32x4* wcol = reinterpret_cast<const u32x4*>(p.w) + (size_t)((co0 >> 5) + wn * NI) * 64 +
-                      (PH ? (size_t)(wave * 4) * tap_stride : 0);
+  constexpr int D = RING ? RING : prefetch_ring(KT * KT * KK, MI * NI);   // weight fragments are fetched D-1 k-steps ahead
+  static_assert((KT * KT * KK) % D == 0, "the ring position must be the same at every chunk start");
+  const int tap_stride = p.cin_blocks * p.cout_blocks * 1024, kk_stride = p.cout_blocks * 1024;   // bytes
+  // byte offset of this wavefront's fragment column (wave-uniform; the lane's 16 bytes are added by the load)
+  const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p.w), 0, p.w_bytes, 0x00020000);
+  const int wcol = ((co0 >> 5) + wn * NI) * 1024 + (PH ? wave * 4 * tap_stride : 0);
+  const int lane16 = lane * 16;
   u32x4 bq[D][NI];
 #pragma unroll
   for (int sp = 0; sp < D - 1; ++sp)
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni) bq[sp][ni] = (wcol + ((sp / KK) * tap_stride + (sp % KK) * kk_stride + ni * 64))[lane];
+    for (int ni = 0; ni < NI; ++ni) bq[sp][ni] = load_fragment(wrsrc, lane16, wcol + (sp / KK) * tap_stride + (sp % KK) * kk_stride + ni * 1024);
 
   // ---- staging: a thread owns NV (pixel, channel-octet) vectors of the halo tile; the octet is the same for all
   const int cvec = tid % VPP;
   const char* xin = reinterpret_cast<const char*>(p.x) + (size_t)n * h_in * w_in * p.cin * sizeof(T);   // uniform base
-  int src_off[NV];          // byte offset of the vector in x (chunk 0), or -1: outside the image / past the tile
+  // Zero padding without per-element work: a vector outside the image is loaded from pixel 0 (a load under a lane
+  // mask would make the compiler wait for it at the end of the branch), activated like any other, and stored to
+  // the spare pixel slot behind the patch; its real slot is zeroed once, here, in both buffers.  A 1x1 convolution
+  // has no halo: what its out-of-image pixels hold only reaches outputs that are never stored.
+  int src_off[NV];          // byte offset of the vector in x (chunk 0)
+  int dst_off[NV];          // element offset of its slot in a staged tile
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     const int v = tid + i * NT;
     const int hp = v / VPP;
     const int hy = hp / HW_, hx = hp % HW_;
     const int gy = ty0 + hy - PAD, gx = tx0 + hx - PAD;
-    src_off[i] = -1;
-    if (v < HP * VPP && gy >= 0 && gy < h_t && gx >= 0 && gx < w_t) {
+    const bool in_patch = v < HP * VPP;
+    const bool inside = in_patch && gy >= 0 && gy < h_t && gx >= 0 && gx < w_t;
+    src_off[i] = 0;
+    if (inside) {
       const int sy = (!PH && p.upsample) ? gy >> 1 : gy, sx = (!PH && p.upsample) ? gx >> 1 : gx;
       src_off[i] = ((sy * w_in + sx) * p.cin + cvec * 8) * (int)sizeof(T);
+    }
+    const bool keep = KS == 1 ? in_patch : inside;
+    dst_off[i] = (keep ? hp : HP) * PS + cvec * 8;
+    if (KS != 1 && in_patch && !inside) {
+      *reinterpret_cast<u32x4*>(s_a + hp * PS + cvec * 8) = u32x4{0u, 0u, 0u, 0u};
+      *reinterpret_cast<u32x4*>(s_a + BUF + hp * PS + cvec * 8) = u32x4{0u, 0u, 0u, 0u};
     }
   }
   // One register set of raw vectors.  The loads of chunk k+1 are issued right after the MFMA sweep of chunk
@@ -373,13 +402,12 @@ void conv_mfma_kernel(MfmaParams p) {
   // before they have landed: the workgroup barrier and the first third of the next sweep cover that), and the
   // vectors are activated and stored into the other LDS buffer in the last two thirds of the sweep of chunk k,
   // a few elements after every M tile's MFMAs, so that this vector-ALU work overlaps the matrix pipe instead of
-  // forming a phase of its own.  Loads are unconditional (vectors outside the image read pixel 0 and are zeroed
-  // afterwards): a load under a lane mask makes the compiler wait for it at the end of the branch.
+  // forming a phase of its own.
   u32x4 raw[NV];
   auto issue = [&](int chunk) {
     const int cb = min(chunk, p.cin / KC - 1) * KC * (int)sizeof(T);   // past the last chunk: a harmless reload
 #pragma unroll
-    for (int i = 0; i < NV; ++i) raw[i] = *reinterpret_cast<const u32x4*>(xin + (unsigned)(max(src_off[i], 0) + cb));
+    for (int i = 0; i < NV; ++i) raw[i] = *reinterpret_cast<const u32x4*>(xin + (unsigned)(src_off[i] + cb));
   };
   // word `part` (two channels) of vector i: scale/shift (+ SiLU) with the table entries of chunk channel c0
   auto activate_word = [&](uint32_t wv, int i, int part, int c0) -> uint32_t {
@@ -389,11 +417,10 @@ void conv_mfma_kernel(MfmaParams p) {
       if constexpr (ACT == 2) { f0 = silu_f(f0); f1 = silu_f(f1); }
       wv = pack2<T>(f0, f1);
     }
-    return src_off[i] >= 0 ? wv : 0u;   // zero padding acts on the activated tensor
+    (void)i;
+    return wv;
   };
-  auto store_vec = [&](int i, T* buf) {
-    *reinterpret_cast<u32x4*>(buf + ((tid + i * NT) / VPP) * PS + cvec * 8) = raw[i];
-  };
+  auto store_vec = [&](int i, T* buf) { *reinterpret_cast<u32x4*>(buf + dst_off[i]) = raw[i]; };
   auto activate_all = [&](int c0, T* buf) {
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
@@ -416,8 +443,8 @@ void conv_mfma_kernel(MfmaParams p) {
   TRACE(1);
   for (int c = 0; c < nchunks; ++c) {
     const bool more = c + 1 < nchunks;
-    const u32x4* bcur = wcol + (size_t)(c * KK) * kk_stride;
-    const u32x4* bnext = more ? bcur + (size_t)KK * kk_stride : bcur;
+    const int bcur = wcol + c * KK * kk_stride;
+    const int bnext = more ? bcur + KK * kk_stride : bcur;
     const T* buf = s_a + (c & 1) * BUF;
     T* nbuf = s_a + ((c + 1) & 1) * BUF;
     const int c0n = (c + 1) * KC;
@@ -438,11 +465,11 @@ void conv_mfma_kernel(MfmaParams p) {
       };
       // the last chunk activates a harmless reload into the buffer nobody reads: one instruction stream, no
       // control flow inside the pinned schedule
-      mfma_chunk<T, MI, NI, KT, KC, HW_, PS, D, true>(buf, a_off, bcur, bnext, tap_stride, kk_stride, lane, bq, acc, slice);
+      mfma_chunk<T, MI, NI, KT, KC, HW_, PS, D, true>(buf, a_off, wrsrc, bcur, bnext, tap_stride, kk_stride, lane16, bq, acc, slice);
       TRACE(3 + 4 * c);
     } else {
       auto none = [](auto) {};
-      mfma_chunk<T, MI, NI, KT, KC, HW_, PS, D, false>(buf, a_off, bcur, bnext, tap_stride, kk_stride, lane, bq, acc, none);
+      mfma_chunk<T, MI, NI, KT, KC, HW_, PS, D, false>(buf, a_off, wrsrc, bcur, bnext, tap_stride, kk_stride, lane16, bq, acc, none);
       TRACE(3 + 4 * c);
       if (more) activate_all(c0n, nbuf);
     }
@@ -472,7 +499,7 @@ void conv_mfma_kernel(MfmaParams p) {
 #endif
 }
 
-template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC, bool PH = false>
+template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC, bool PH = false, int RING = 0>
 int launch_cfg(const ConvArgs& a, hipStream_t s) {
   constexpr int PAD = PH ? 1 : KS / 2;
   constexpr int HP = (TW + 2 * PAD) * (TH + 2 * PAD);
@@ -487,6 +514,7 @@ int launch_cfg(const ConvArgs& a, hipStream_t s) {
   p.tiles_x = (w_t + TW - 1) / TW; p.tiles_y = (h_t + TH - 1) / TH; p.ntiles = (a.cout + TN - 1) / TN;
   p.total = p.tiles_x * p.tiles_y * p.ntiles * a.n;
   p.cin_blocks = packed_cin_blocks(a.cin); p.cout_blocks = packed_cout_blocks(a.cout); p.y_nchw = a.y_nchw;
+  p.w_bytes = (int)(packed_elems(PH ? 16 : KS * KS, a.cout, a.cin) * sizeof(T));
   p.stats = (Moments*)a.stats_ws; p.stats_groups = a.stats_groups; p.stats_cpg = a.stats_groups > 0 ? a.cout / a.stats_groups : 1;
   p.stats_slots = p.tiles_x * p.tiles_y * WM;
 #ifdef WMDEC_TRACE
@@ -494,13 +522,13 @@ int launch_cfg(const ConvArgs& a, hipStream_t s) {
 #endif
   constexpr int NT = 64 * WM * WN;
   constexpr int NV = (HP * (KC / 8) + NT - 1) / NT;
-  size_t smem = (((size_t)2 * (NV * NT / (KC / 8)) * (KC + 8) * 2 + 15) & ~(size_t)15) + (size_t)a.cin * sizeof(float2);
+  size_t smem = (((size_t)2 * tile_pixel_slots(NV * NT / (KC / 8), HP) * (KC + 8) * 2 + 15) & ~(size_t)15) + (size_t)a.cin * sizeof(float2);
   const size_t patch = (size_t)(WM * WN) * patch_floats(NI) * sizeof(float);   // epilogue patches of the wavefronts
   if (smem < patch) smem = patch;
   WMDEC_REQUIRE(smem <= 80 * 1024, WMDEC_ERR_UNSUPPORTED, "conv_mfma: %zu bytes of LDS needed", smem);
-  void (*kern)(MfmaParams) = !p.norm ? conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 0, PH>
-                             : (a.silu ? conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 2, PH>
-                                       : conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 1, PH>);
+  void (*kern)(MfmaParams) = !p.norm ? conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 0, PH, RING>
+                             : (a.silu ? conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 2, PH, RING>
+                                       : conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 1, PH, RING>);
   static bool attr_set[3] = {false, false, false};   // per instantiation and activation mode
   const int mode = !p.norm ? 0 : (a.silu ? 2 : 1);
   if (!attr_set[mode]) {
@@ -529,6 +557,9 @@ constexpr TileShape kTiles[] = {
                          //     compute units empty run two wavefronts per SIMD, so vector-ALU work hides under another's MFMAs
     {8, 16, 1, 4, 1},    // 11: 128 x 128, every wavefront all pixels x 32 channels: a weight fragment feeds four MFMAs
                          //     (two in shape 4), which halves the load on the vector L1 (64 B/clk per compute unit)
+    {8, 16, 2, 2, 2},    // 12: shape 4 with a weight ring of 9 k-steps
+    {8, 16, 2, 4, 1},    // 13: shape 10 with a ring of 9
+    {8, 16, 2, 4, 1},    // 14: shape 10 with a ring of 18
 };
 
 // which tile shape a launch uses (3x3: any of the above; 1x1: 0, 1 or 2)
@@ -543,7 +574,7 @@ int pick_tile(const ConvArgs& a) {
     // 256-pixel tiles when that still gives three per compute unit; else 128-pixel tiles, with one weight
     // fragment per four MFMAs (shape 11) unless the layer leaves compute units empty anyway (shape 4)
     const long work = px * (a.cout / 128);
-    int t = (g_tile == 0 || g_tile == 4 || g_tile == 6 || g_tile == 8 || g_tile == 10 || g_tile == 11) ? g_tile
+    int t = (g_tile == 0 || g_tile == 4 || g_tile == 6 || g_tile == 8 || g_tile == 10 || g_tile == 11 || g_tile == 12 || g_tile == 13 || g_tile == 14) ? g_tile
             : (n128 && work >= 256L * 256 * 3) ? 0 : (n128 ? (work >= 128L * 256 * 2 ? 11 : 4) : 6);
     if (!n128) t = 6;
     return t;
@@ -562,6 +593,9 @@ int launch_3x3(const ConvArgs& a, hipStream_t s) {
     case 9: return launch_cfg<T, TO, 8, 16, 4, 1, 2, 3, 32, true>(a, s);
     case 10: return launch_cfg<T, TO, 8, 16, 2, 4, 1, 3, 32>(a, s);
     case 11: return launch_cfg<T, TO, 8, 16, 1, 4, 1, 3, 32>(a, s);
+    case 12: return launch_cfg<T, TO, 8, 16, 2, 2, 2, 3, 32, false, 9>(a, s);
+    case 13: return launch_cfg<T, TO, 8, 16, 2, 4, 1, 3, 32, false, 9>(a, s);
+    case 14: return launch_cfg<T, TO, 8, 16, 2, 4, 1, 3, 32, false, 18>(a, s);
     default: return launch_cfg<T, TO, 8, 32, 4, 1, 1, 3, 32>(a, s);
   }
 }
@@ -630,7 +664,7 @@ const char* conv_mfma_label(const ConvArgs& a) {
     if (a.cin % 64 == 0) kc = 64;
     else if (t == 0) t = 1;
     if (t != 0 && t != 1) t = 2;
-  } else if (t != 0 && t != 4 && t != 6 && t != 8 && t != 9 && t != 10 && t != 11) {
+  } else if (t != 0 && t != 4 && t != 6 && t != 8 && t != 9 && t != 10 && t != 11 && t != 12 && t != 13 && t != 14) {
     t = 7;
   }
   const TileShape& ts = kTiles[t];

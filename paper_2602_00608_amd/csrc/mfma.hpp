@@ -39,6 +39,15 @@ template <> struct Mma<f16_t> {
 template <typename T> __device__ __forceinline__ uint32_t pack2(float a, float b) {
   return (uint32_t)from_float<T>(a).bits | ((uint32_t)from_float<T>(b).bits << 16);
 }
+// f16: built as a two-element vector so that the compiler can convert straight into the low / high half
+// (v_fma_mixlo_f16 / v_fma_mixhi_f16, v_cvt_pk) instead of converting, shifting and or-ing
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+template <> __device__ __forceinline__ uint32_t pack2<f16_t>(float a, float b) {
+  f16x2_t v;
+  v.x = (_Float16)a;
+  v.y = (_Float16)b;
+  return __builtin_bit_cast(uint32_t, v);
+}
 template <typename T> __device__ __forceinline__ float unpack_lo(uint32_t w) { return to_float(T{(uint16_t)(w & 0xffffu)}); }
 template <typename T> __device__ __forceinline__ float unpack_hi(uint32_t w) { return to_float(T{(uint16_t)(w >> 16)}); }
 
