@@ -219,6 +219,12 @@ constexpr int prefetch_ring(int steps, int room) {
   return steps % 3 == 0 ? 3 : (steps % 4 == 0 ? 4 : 2);
 }
 
+// silu(t) from u = -log2(e) * t (see the scale/shift table)
+__device__ __forceinline__ float silu_from_scaled(float u) {
+  constexpr float k = -1.4426950408889634f;
+  return u * __builtin_amdgcn_rcpf(fmaf(__builtin_amdgcn_exp2f(u), k, k));
+}
+
 // One weight fragment (1 KiB, a lane's 16 bytes at lane16 = 16 * lane) at byte offset `off` of the packed weights.
 // A buffer load takes the wave-uniform offset in a scalar register, so the address costs no vector-ALU work
 // (a global load would add the 64-bit base per fragment), and offsets past the blob read zeros instead of faulting.
@@ -328,13 +334,16 @@ void conv_mfma_kernel(MfmaParams p) {
   const int h_in = p.upsample ? p.h >> 1 : p.h, w_in = p.upsample ? p.w_out >> 1 : p.w_out;
   const int h_t = PH ? h_in : p.h, w_t = PH ? w_in : p.w_out;   // the grid the tiles live on
 
-  // per-channel scale/shift table: a = gamma*rstd, b = beta - mean*a
+  // per-channel scale/shift table: a = gamma*rstd, b = beta - mean*a.  With SiLU the table holds -log2(e) * (a, b):
+  // the staged value is u = -log2(e) * t, from which silu(t) = t / (1 + 2^u) = u / (-log2(e) - log2(e) * 2^u) takes
+  // one exp2, one fma, one reciprocal and one multiply
   if constexpr (ACT > 0) {
     const int cpg = p.cin / p.groups;
+    const float k = ACT == 2 ? -1.4426950408889634f : 1.0f;
     for (int c = tid; c < p.cin; c += NT) {
       const int g = c / cpg;
       const float a = p.gamma[c] * p.rstd[n * p.groups + g];
-      s_ab[c] = make_float2(a, p.beta[c] - p.mean[n * p.groups + g] * a);
+      s_ab[c] = make_float2(k * a, k * (p.beta[c] - p.mean[n * p.groups + g] * a));
     }
   }
 
@@ -414,7 +423,7 @@ void conv_mfma_kernel(MfmaParams p) {
     if constexpr (ACT > 0) {
       const f32x4 ab = *reinterpret_cast<const f32x4*>(s_ab + c0 + cvec * 8 + 2 * part);   // (a0, b0, a1, b1)
       float f0 = fmaf(unpack_lo<T>(wv), ab[0], ab[1]), f1 = fmaf(unpack_hi<T>(wv), ab[2], ab[3]);
-      if constexpr (ACT == 2) { f0 = silu_f(f0); f1 = silu_f(f1); }
+      if constexpr (ACT == 2) { f0 = silu_from_scaled(f0); f1 = silu_from_scaled(f1); }
       wv = pack2<T>(f0, f1);
     }
     (void)i;
