@@ -93,9 +93,9 @@ def main():
     fps = args.batch * args.steps / elapsed
     assert bool(torch.isfinite(out).all())
 
-    # ---- roofline of the dominant kernel: every graph step again, `reps` launches back to back between two HIP
-    # events on the stream the kernels run on (the workspace still holds the tensors of the last run, and no step
-    # overwrites its own inputs), grouped by the kernel that executes the step
+    # ---- roofline of the dominant kernel: every graph step again, in plan order, `reps` launches back to back
+    # between two HIP events on the stream the kernels run on (each step then sees the tensors of a real run),
+    # grouped by the kernel that executes the step
     info = dec.step_info()
     reps = 10
     fam = {}

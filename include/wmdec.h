@@ -236,8 +236,12 @@ double decoder_flops_per_frame(const wmdec_decoder* dec);
  * decoder_time_step measures one step without that overhead: after a
  * decoder_run with the same arguments has filled the workspace, it enqueues
  * step `step` `reps` times back to back between two HIP events on `stream`,
- * waits, and returns the mean milliseconds per launch (the step's inputs are
- * not modified by it, so every repetition does the same work). */
+ * waits, and returns the mean milliseconds per launch.  The step runs on what
+ * the workspace holds; steps timed in plan order see the tensors of a real
+ * run, except that the second convolution of a channel-changing ResBlock
+ * accumulates onto its shortcut in place, once per repetition.  The timing
+ * does not depend on the values; call decoder_run again before using the
+ * frame or the workspace tensors. */
 int decoder_set_profiling(wmdec_decoder* dec, int enable);
 int decoder_num_steps(const wmdec_decoder* dec);
 int decoder_step_info(const wmdec_decoder* dec, int index, const char** kernel, double* flops, double* bytes);

@@ -76,6 +76,24 @@ def test_flops_independent_count():
     dec.close()
 
 
+def test_step_accounting_adds_up():
+    """The per-step figures the benchmark prices kernels with: their FLOPs sum to the frame total, every step
+    names its kernel, convolutions carry the instantiation, and the byte count of a ResBlock convolution is
+    input + residual + output + weights, each once."""
+    dec = wmdec.Decoder()
+    info = dec.step_info()
+    assert abs(sum(f for _, f, _ in info) - dec.flops_per_frame()) / dec.flops_per_frame() < 1e-12
+    assert all(k for k, _, _ in info)
+    convs = [(k, f, b) for k, f, b in info if k.startswith("conv_mfma_kernel<")]
+    assert len(convs) >= 36 and all(k.endswith(">") for k, _, _ in convs)
+    # last ResBlock convolution at 480x720: 128 -> 128, f16, with residual
+    want_flops = 2.0 * 9 * 128 * 128 * 480 * 720
+    want_bytes = 3 * 480 * 720 * 128 * 2 + 9 * 128 * 128 * 2
+    assert any(f == want_flops and b == want_bytes for _, f, b in convs)
+    assert sum(1 for k, _, _ in info if k == "gn_finalize") + sum(1 for k, _, _ in info if k == "gn_stats_vec") == 30
+    dec.close()
+
+
 def test_argument_errors_are_reported_without_a_gpu():
     l = wmdec.lib()
     assert l.wmdec_gn_stats(None, 0, 1, 1, 1, 32, 32, 1e-6, None, None, None, 0, None) == wmdec.ERR_INVALID_ARG
@@ -95,6 +113,11 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert l.wmdec_conv_packed_bytes(64, 64, 3, wmdec.F32) == 9 * 64 * 64 * 4
     assert l.wmdec_conv_packed_bytes(3, 4, 3, wmdec.BF16) == 9 * 32 * 16 * 2   # padded to 32 x 16 fragments
     assert l.wmdec_conv_packed_bytes(64, 64, 2, wmdec.F32) == 0
+    # upsampling convolution: the 9-tap pack plus the 16-tap phase pack
+    assert l.wmdec_upconv_packed_bytes(64, 64, wmdec.F16) == (9 + 16) * 64 * 64 * 2
+    assert l.wmdec_upconv_packed_bytes(64, 64, 9) == 0
+    assert l.wmdec_pack_upconv_weights(p, wmdec.F16, 64, 64, 2 * p, wmdec.F16, None) == wmdec.ERR_INVALID_ARG   # source type
+    assert l.wmdec_pack_upconv_weights(p, wmdec.F32, 64, 64, 2 * p + 8, wmdec.F16, None) == wmdec.ERR_INVALID_ARG   # alignment
     assert l.wmdec_status_string(wmdec.ERR_WORKSPACE) == b"workspace missing or too small"
     cfg = wmdec.decoder_default_config()
     cfg.level_channels[2] = 250
@@ -106,6 +129,9 @@ def test_argument_errors_are_reported_without_a_gpu():
     dec = wmdec.Decoder()
     assert l.decoder_run(dec.handle, p, p, p, 9, None) == wmdec.ERR_INVALID_ARG
     assert l.decoder_run(dec.handle, p, p, p, 1, None) == wmdec.ERR_WORKSPACE
+    ms = ctypes.c_float()
+    assert l.decoder_time_step(dec.handle, p, p, p, 1, 0, 1, ctypes.byref(ms), None) == wmdec.ERR_INVALID_ARG   # no run yet
+    assert l.decoder_time_step(dec.handle, p, p, p, 1, 999, 1, ctypes.byref(ms), None) == wmdec.ERR_INVALID_ARG
     dec.close()
 
 

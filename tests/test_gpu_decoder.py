@@ -149,6 +149,34 @@ def workload4():
     return weights, z, want
 
 
+def test_time_step_repeats_a_step_without_changing_the_frame():
+    """decoder_time_step launches one step of the plan several times on whatever the workspace holds; it must not
+    disturb anything a later full run depends on (ticket counters, packed weights, the plan itself)."""
+    cfg = small_cfg(wmdec.F16)
+    spec = synth.decoder_weight_spec(level_channels=(512, 128, 64, 32), resblocks_per_level=2)
+    weights = synth.draw_params(spec, synth.weight_seed(9), random_affine=True)
+    z = synth.latent_sequence(workload=9, frames=1, h=7, w=9)
+    dec = wmdec.Decoder(cfg)
+    packed = torch.empty(dec.packed_bytes(), dtype=torch.uint8, device="cuda")
+    dec.pack_weights(make_blob(dec, weights), packed)
+    ws = torch.empty(dec.workspace_bytes(1), dtype=torch.uint8, device="cuda")
+    dec.set_workspace(ws)
+    zd = torch.from_numpy(synth.bf16_bits(z).view(np.int16)).view(torch.bfloat16).cuda()
+    scale = 2 ** (cfg.num_levels - 1)
+    out = torch.empty((1, cfg.out_c, cfg.latent_h * scale, cfg.latent_w * scale), dtype=torch.float32, device="cuda")
+    dec.run(zd, packed, out)
+    torch.cuda.synchronize()
+    first = out.clone()
+    info = dec.step_info()
+    for i in range(len(info)):
+        ms = dec.time_step(zd, packed, out, i, 2)
+        assert ms > 0.0, (i, info[i][0])
+    dec.run(zd, packed, out)
+    torch.cuda.synchronize()
+    assert torch.equal(out, first)
+    dec.close()
+
+
 def test_decoder_full_size_f16(workload4):
     """Workload 4: z[1,4,60,90] -> [1,3,480,720], full decoder, against the fp64 oracle."""
     weights, z, want = workload4

@@ -240,7 +240,10 @@ def run_attention(dtype, n, h, w, seed):
     return G.host_nchw(y), want, x
 
 
-@pytest.mark.parametrize("dtype,n,h,w", [("f16", 1, 5, 7), ("bf16", 2, 9, 8), ("f16", 1, 1, 1), ("bf16", 1, 16, 20)])
+# 5x7, 1x1: one ragged query block; 9x8, 16x20: several query blocks with a ragged last one and two key splits;
+# 13x37 = 481 tokens: 8 query blocks (the last holds one query), 16 key blocks over 8 splits
+@pytest.mark.parametrize("dtype,n,h,w", [("f16", 1, 5, 7), ("bf16", 2, 9, 8), ("f16", 1, 1, 1), ("bf16", 1, 16, 20),
+                                         ("f16", 2, 13, 37)])
 def test_attention_small(dtype, n, h, w):
     got, want, x = run_attention(dtype, n, h, w, 20)
     assert ref.rel_err(got, want) <= G.TOL[dtype]
