@@ -51,5 +51,18 @@ def build(force=True, jobs=8):
     return LIB
 
 
+def build_diag():
+    """The stand-alone diagnostic that measures what the matrix pipe sustains on this machine."""
+    exe = os.path.join(HERE, "mfma_ceiling")
+    subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17",
+                           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                           os.path.join(CSRC, "diag", "mfma_ceiling.hip"), "-o", exe],
+                          stderr=subprocess.DEVNULL)
+    return exe
+
+
 if __name__ == "__main__":
-    print(build(force="--incremental" not in sys.argv))
+    if "--diag" in sys.argv:
+        print(build_diag())
+    else:
+        print(build(force="--incremental" not in sys.argv))
