@@ -287,10 +287,8 @@ constexpr int wave_m_tiles(int th, int tw, int wm, bool ph) { return ph ? th * t
 // spare: vectors that lie outside the image (or past the patch) are stored there, where no MFMA reads them.
 constexpr int tile_pixel_slots(int stored, int hp) { return stored > hp ? stored : hp + 1; }
 
-// RING: length of the weight prefetch ring (0: the default for the tile); a long ring is for layers with too few
-// workgroups to keep more than one wavefront per SIMD busy, where a k-step is short against the L2 latency
-template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC, int ACT, bool PH = false, int RING = 0>
-__global__ __launch_bounds__(64 * WM * WN, WM * WN == 8 ? 1 : ((wave_m_tiles(TH, TW, WM, PH) * NI <= 4 && RING == 0) ? 3 : 2))
+template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC, int ACT, bool PH = false>
+__global__ __launch_bounds__(64 * WM * WN, WM * WN == 8 ? 1 : (wave_m_tiles(TH, TW, WM, PH) * NI <= 4 ? 3 : 2))
 void conv_mfma_kernel(MfmaParams p) {
   static_assert(WM * WN == 4 || WM * WN == 8, "four or eight wavefronts");
   constexpr int NT = 64 * WM * WN;               // threads of the workgroup
@@ -364,7 +362,7 @@ void conv_mfma_kernel(MfmaParams p) {
     a_off[mi] = (ty * HW_ + tx) * PS + 8 * lk + (PH ? ((wave >> 1) * HW_ + (wave & 1)) * PS : 0);
   }
   constexpr int KK = KC / 16;
-  constexpr int D = RING ? RING : prefetch_ring(KT * KT * KK, MI * NI);   // weight fragments are fetched D-1 k-steps ahead
+  constexpr int D = prefetch_ring(KT * KT * KK, MI * NI);   // weight fragments are fetched D-1 k-steps ahead
   static_assert((KT * KT * KK) % D == 0, "the ring position must be the same at every chunk start");
   const int tap_stride = p.cin_blocks * p.cout_blocks * 1024, kk_stride = p.cout_blocks * 1024;   // bytes
   // byte offset of this wavefront's fragment column (wave-uniform; the lane's 16 bytes are added by the load)
@@ -508,7 +506,7 @@ void conv_mfma_kernel(MfmaParams p) {
 #endif
 }
 
-template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC, bool PH = false, int RING = 0>
+template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC, bool PH = false>
 int launch_cfg(const ConvArgs& a, hipStream_t s) {
   constexpr int PAD = PH ? 1 : KS / 2;
   constexpr int HP = (TW + 2 * PAD) * (TH + 2 * PAD);
@@ -535,9 +533,9 @@ int launch_cfg(const ConvArgs& a, hipStream_t s) {
   const size_t patch = (size_t)(WM * WN) * patch_floats(NI) * sizeof(float);   // epilogue patches of the wavefronts
   if (smem < patch) smem = patch;
   WMDEC_REQUIRE(smem <= 80 * 1024, WMDEC_ERR_UNSUPPORTED, "conv_mfma: %zu bytes of LDS needed", smem);
-  void (*kern)(MfmaParams) = !p.norm ? conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 0, PH, RING>
-                             : (a.silu ? conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 2, PH, RING>
-                                       : conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 1, PH, RING>);
+  void (*kern)(MfmaParams) = !p.norm ? conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 0, PH>
+                             : (a.silu ? conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 2, PH>
+                                       : conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 1, PH>);
   static bool attr_set[3] = {false, false, false};   // per instantiation and activation mode
   const int mode = !p.norm ? 0 : (a.silu ? 2 : 1);
   if (!attr_set[mode]) {
@@ -560,15 +558,11 @@ constexpr TileShape kTiles[] = {
     {16, 16, 2, 2, 2},   // 5: 256 x 128, 16x16 patch
     {8, 16, 4, 1, 2},    // 6: 128 x 64, 8x16 patch
     {8, 32, 4, 1, 1},    // 7: 256 x 32 (few output channels: the frame)
-    {8, 32, 1, 4, 1},    // 8: 256 x 128, every wavefront all pixels x 32 channels: no weight fragment is loaded twice
+    {8, 32, 1, 4, 1},    // 8: 256 x 128 with wavefronts 1x4 (measured: no gain over shape 0; not instantiated)
     {8, 16, 4, 1, 2},    // 9: phase-decomposed upsampling convolution: 8x16 input pixels (16x32 outputs) x 64 channels
-    {8, 16, 2, 4, 1},    // 10: 128 x 128 with eight wavefronts (64 pixels x 32 channels each): small layers that leave
-                         //     compute units empty run two wavefronts per SIMD, so vector-ALU work hides under another's MFMAs
+    {8, 16, 2, 4, 1},    // 10: 128 x 128 with eight wavefronts (measured: no gain on the small layers; not instantiated)
     {8, 16, 1, 4, 1},    // 11: 128 x 128, every wavefront all pixels x 32 channels: a weight fragment feeds four MFMAs
                          //     (two in shape 4), which halves the load on the vector L1 (64 B/clk per compute unit)
-    {8, 16, 2, 2, 2},    // 12: shape 4 with a weight ring of 9 k-steps
-    {8, 16, 2, 4, 1},    // 13: shape 10 with a ring of 9
-    {8, 16, 2, 4, 1},    // 14: shape 10 with a ring of 18
 };
 
 // which tile shape a launch uses (3x3: any of the above; 1x1: 0, 1 or 2)
@@ -583,7 +577,7 @@ int pick_tile(const ConvArgs& a) {
     // 256-pixel tiles when that still gives three per compute unit; else 128-pixel tiles, with one weight
     // fragment per four MFMAs (shape 11) unless the layer leaves compute units empty anyway (shape 4)
     const long work = px * (a.cout / 128);
-    int t = (g_tile == 0 || g_tile == 4 || g_tile == 6 || g_tile == 8 || g_tile == 10 || g_tile == 11 || g_tile == 12 || g_tile == 13 || g_tile == 14) ? g_tile
+    int t = (g_tile == 0 || g_tile == 4 || g_tile == 6 || g_tile == 11) ? g_tile
             : (n128 && work >= 256L * 256 * 3) ? 0 : (n128 ? (work >= 128L * 256 * 2 ? 11 : 4) : 6);
     if (!n128) t = 6;
     return t;
@@ -598,13 +592,8 @@ int launch_3x3(const ConvArgs& a, hipStream_t s) {
     case 0: return launch_cfg<T, TO, 8, 32, 2, 2, 2, 3, 32>(a, s);
     case 4: return launch_cfg<T, TO, 8, 16, 2, 2, 2, 3, 32>(a, s);
     case 6: return launch_cfg<T, TO, 8, 16, 4, 1, 2, 3, 32>(a, s);
-    case 8: return launch_cfg<T, TO, 8, 32, 1, 4, 1, 3, 32>(a, s);
     case 9: return launch_cfg<T, TO, 8, 16, 4, 1, 2, 3, 32, true>(a, s);
-    case 10: return launch_cfg<T, TO, 8, 16, 2, 4, 1, 3, 32>(a, s);
     case 11: return launch_cfg<T, TO, 8, 16, 1, 4, 1, 3, 32>(a, s);
-    case 12: return launch_cfg<T, TO, 8, 16, 2, 2, 2, 3, 32, false, 9>(a, s);
-    case 13: return launch_cfg<T, TO, 8, 16, 2, 4, 1, 3, 32, false, 9>(a, s);
-    case 14: return launch_cfg<T, TO, 8, 16, 2, 4, 1, 3, 32, false, 18>(a, s);
     default: return launch_cfg<T, TO, 8, 32, 4, 1, 1, 3, 32>(a, s);
   }
 }
@@ -673,7 +662,7 @@ const char* conv_mfma_label(const ConvArgs& a) {
     if (a.cin % 64 == 0) kc = 64;
     else if (t == 0) t = 1;
     if (t != 0 && t != 1) t = 2;
-  } else if (t != 0 && t != 4 && t != 6 && t != 8 && t != 9 && t != 10 && t != 11 && t != 12 && t != 13 && t != 14) {
+  } else if (t != 0 && t != 4 && t != 6 && t != 9 && t != 11) {
     t = 7;
   }
   const TileShape& ts = kTiles[t];
