@@ -56,6 +56,30 @@ def test_gn_stats_deterministic():
     assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
 
 
+def test_gn_stats_workspace_reuse_across_tensors():
+    """One workspace (ticket counters zeroed once) serves many calls on different tensors and shapes of the same
+    batch size, back to back on one stream: every call must see only its own partial moments and leave the
+    counters at zero for the next."""
+    n, groups, eps = 2, 32, 1e-6
+    shapes = [(128, 61, 47), (256, 30, 44), (512, 9, 13), (128, 120, 90), (64, 5, 7)]
+    ws = torch.zeros(max(wmdec.gn_stats_workspace_bytes(n, h, w, c, groups) for c, h, w in shapes), dtype=torch.uint8, device="cuda")
+    xs, outs = [], []
+    for rep in range(4):
+        for i, (c, h, w) in enumerate(shapes):
+            x = G.stored(rng(100 + 10 * rep + i).standard_normal((n, c, h, w)) * (1.0 + i) - rep, "f16")
+            xd = G.dev_nhwc(x, "f16")
+            mean = torch.empty(n * groups, dtype=torch.float32, device="cuda")
+            rstd = torch.empty(n * groups, dtype=torch.float32, device="cuda")
+            wmdec.gn_stats(xd, groups, eps, mean, rstd, ws)
+            xs.append(x); outs.append((mean, rstd, xd))
+    torch.cuda.synchronize()
+    for x, (mean, rstd, _) in zip(xs, outs):
+        wm, wr = ref.gn_stats(x, groups, eps)
+        assert np.max(np.abs(mean.cpu().numpy() - wm.ravel()) * wr.ravel()) < 2e-5
+        assert np.max(np.abs(rstd.cpu().numpy() / wr.ravel() - 1.0)) < 2e-5
+    assert int(ws[:256].view(torch.int32).abs().sum()) == 0   # tickets back at zero
+
+
 # ------------------------------------------------------------------ a3': nearest-2x upsample (bit exact)
 @pytest.mark.parametrize("dtype,n,c,h,w", [("bf16", 1, 256, 120, 180), ("f32", 2, 3, 5, 7), ("f16", 1, 8, 1, 1),
                                            ("bf16", 2, 20, 6, 3), ("bf16", 1, 5, 4, 9)])
