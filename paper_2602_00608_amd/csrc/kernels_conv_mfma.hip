@@ -282,13 +282,19 @@ __device__ __forceinline__ void mfma_chunk(const T* buf, const int (&a_off)[MI],
 // 2x2 convolution over input rows i + py - 1 .. i + py and columns j + px - 1 .. j + px with the phase's pre-summed
 // weights (taps 4 * w .. 4 * w + 3 of the 16-tap phase pack): 4/9 of the multiplications of the 3x3 form.
 constexpr int wave_m_tiles(int th, int tw, int wm, bool ph) { return ph ? th * tw / 32 : th * tw / 32 / wm; }
+// Workgroups per compute unit the register budget is sized for: three for the small accumulator tiles, except the
+// 2x2-wavefront 128x128 shape, which is only picked for layers with at most two workgroups per compute unit and
+// uses the registers for a longer prefetch instead.
+constexpr int resident_workgroups(int acc_tiles, int wm, int wn) {
+  return wm * wn == 8 ? 1 : (acc_tiles <= 4 && !(wm == 2 && wn == 2) ? 3 : 2);
+}
 
 // Pixel slots of a staged tile: every thread stores all its NV vectors, and at least one slot behind the patch is
 // spare: vectors that lie outside the image (or past the patch) are stored there, where no MFMA reads them.
 constexpr int tile_pixel_slots(int stored, int hp) { return stored > hp ? stored : hp + 1; }
 
 template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC, int ACT, bool PH = false>
-__global__ __launch_bounds__(64 * WM * WN, WM * WN == 8 ? 1 : (wave_m_tiles(TH, TW, WM, PH) * NI <= 4 ? 3 : 2))
+__global__ __launch_bounds__(64 * WM * WN, resident_workgroups(wave_m_tiles(TH, TW, WM, PH) * NI, WM, WN))
 void conv_mfma_kernel(MfmaParams p) {
   static_assert(WM * WN == 4 || WM * WN == 8, "four or eight wavefronts");
   constexpr int NT = 64 * WM * WN;               // threads of the workgroup
@@ -416,16 +422,23 @@ void conv_mfma_kernel(MfmaParams p) {
 #pragma unroll
     for (int i = 0; i < NV; ++i) raw[i] = *reinterpret_cast<const u32x4*>(xin + (unsigned)(src_off[i] + cb));
   };
-  // word `part` (two channels) of vector i: scale/shift (+ SiLU) with the table entries of chunk channel c0
-  auto activate_word = [&](uint32_t wv, int i, int part, int c0) -> uint32_t {
+  // word (two channels) of a staged vector: scale/shift (+ SiLU) with the table entries ab = (a0, b0, a1, b1)
+  auto activate_with = [&](uint32_t wv, const f32x4& ab) -> uint32_t {
     if constexpr (ACT > 0) {
-      const f32x4 ab = *reinterpret_cast<const f32x4*>(s_ab + c0 + cvec * 8 + 2 * part);   // (a0, b0, a1, b1)
       float f0 = fmaf(unpack_lo<T>(wv), ab[0], ab[1]), f1 = fmaf(unpack_hi<T>(wv), ab[2], ab[3]);
       if constexpr (ACT == 2) { f0 = silu_from_scaled(f0); f1 = silu_from_scaled(f1); }
       wv = pack2<T>(f0, f1);
     }
-    (void)i;
     return wv;
+  };
+  // table entries of word `part` of this thread's channel octet in the chunk that starts at channel c0
+  auto table_entry = [&](int part, int c0) -> f32x4 {
+    if constexpr (ACT > 0) return *reinterpret_cast<const f32x4*>(s_ab + c0 + cvec * 8 + 2 * part);
+    else return f32x4{0.f, 0.f, 0.f, 0.f};
+  };
+  auto activate_word = [&](uint32_t wv, int i, int part, int c0) -> uint32_t {
+    (void)i;
+    return activate_with(wv, table_entry(part, c0));
   };
   auto store_vec = [&](int i, T* buf) { *reinterpret_cast<u32x4*>(buf + dst_off[i]) = raw[i]; };
   auto activate_all = [&](int c0, T* buf) {
@@ -437,6 +450,8 @@ void conv_mfma_kernel(MfmaParams p) {
     }
   };
   const int nchunks = p.cin / KC;
+  constexpr bool AHEAD = MI * NI <= 4;   // registers to spare for table entries fetched ahead
+  f32x4 abv[2];   // table entries of the part being activated and of the next one (sliced activation)
 
   TRACE(0);
 #ifdef WMDEC_TRACE
@@ -457,16 +472,29 @@ void conv_mfma_kernel(MfmaParams p) {
     const int c0n = (c + 1) * KC;
     TRACE(2 + 4 * c);
     if constexpr (SLICED) {
-      // slots FIRST .. SLOTS-1 share the NV*4 words of the next chunk evenly
+      // Slots FIRST .. SLOTS-1 share the NV*4 words of the next chunk evenly.  All vectors of a thread hold the same
+      // channel octet, so the words are taken part by part (word `part` of every vector, then the next part) and
+      // the four table entries of the octet are read from LDS once each, one part ahead of their first use: a read
+      // issued right where it is needed would expose the LDS latency in every slot.  (The 256-pixel tiles have no
+      // eight registers to spare for that and read the entry per word.)
       auto slice = [&](auto slot_c) {
         constexpr int slot = decltype(slot_c)::value;
         constexpr int FIRST = SLOTS / 3, SPAN = SLOTS - FIRST, NW = NV * 4;
+        if constexpr (AHEAD && slot == FIRST - 1) abv[0] = table_entry(0, c0n);
         if constexpr (slot >= FIRST) {
           constexpr int w0 = (slot - FIRST) * NW / SPAN, w1 = (slot - FIRST + 1) * NW / SPAN;
           static_for<w1 - w0>([&](auto k_c) {
-            constexpr int wi = w0 + decltype(k_c)::value, i = wi / 4, part = wi % 4;
-            raw[i][part] = activate_word(raw[i][part], i, part, c0n);
-            if constexpr (part == 3) store_vec(i, nbuf);
+            constexpr int wi = w0 + decltype(k_c)::value;
+            if constexpr (AHEAD) {
+              constexpr int part = wi / NV, i = wi % NV;
+              if constexpr (i == 0 && part < 3) abv[(part + 1) & 1] = table_entry(part + 1, c0n);
+              raw[i][part] = activate_with(raw[i][part], abv[part & 1]);
+              if constexpr (part == 3) store_vec(i, nbuf);
+            } else {
+              constexpr int i = wi / 4, part = wi % 4;
+              raw[i][part] = activate_word(raw[i][part], i, part, c0n);
+              if constexpr (part == 3) store_vec(i, nbuf);
+            }
           });
         }
       };
