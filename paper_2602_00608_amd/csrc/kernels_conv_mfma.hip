@@ -239,7 +239,9 @@ __device__ __forceinline__ u32x4 load_fragment(__amdgpu_buffer_rsrc_t rsrc, int 
 // that consumed it, which gives the LDS read the rest of the step to land.  The scheduling
 // barriers pin that order: without them the compiler sinks every load to just before its use
 // and each k-step pays a full memory latency.
-template <typename T, int MI, int NI, int KS, int KC, int HW_, int PS, int D, bool SLICED, typename Slice>
+// VALU_PER_MFMA: -1 pins the order as written (slot hook after the MFMAs of an M tile); >= 0 asks the scheduler to
+// interleave that many vector-ALU instructions behind every MFMA of a k-step.
+template <typename T, int MI, int NI, int KS, int KC, int HW_, int PS, int D, bool SLICED, int VALU_PER_MFMA, typename Slice>
 __device__ __forceinline__ void mfma_chunk(const T* buf, const int (&a_off)[MI], __amdgpu_buffer_rsrc_t wrsrc, int bcur, int bnext,
                                            int tap_stride, int kk_stride, int lane16, u32x4 (&bq)[D][NI],
                                            f32x16 (&acc)[MI][NI], Slice&& slice) {
@@ -269,9 +271,21 @@ __device__ __forceinline__ void mfma_chunk(const T* buf, const int (&a_off)[MI],
         af[mi] = *reinterpret_cast<const u32x4*>(buf + a_off[mi] + ((tap / KS) * HW_ + tap % KS) * PS + kk * 16);
       }
       if constexpr (SLICED) slice(std::integral_constant<int, s * MI + mi>{});
-      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (VALU_PER_MFMA < 0) __builtin_amdgcn_sched_barrier(0);
     };
     static_for<MI>(tile);
+    if constexpr (VALU_PER_MFMA >= 0) {
+      // The whole k-step is one scheduling region; spell out the issue order inside it: after every MFMA the A
+      // refresh that belongs to it (one LDS read per NI MFMAs) and an equal share of the step's activation work,
+      // so that each MFMA's 32 cycles in the matrix pipe cover vector-ALU work instead of the next MFMA's wait.
+      static_for<MI * NI>([&](auto j_c) {
+        constexpr int j = decltype(j_c)::value;
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                       // one MFMA
+        if constexpr (j % NI == NI - 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+        if constexpr (VALU_PER_MFMA > 0) __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER_MFMA, 0);
+      });
+      __builtin_amdgcn_sched_barrier(0);
+    }
   };
   static_for<STEPS>(step);
 }
@@ -451,6 +465,11 @@ void conv_mfma_kernel(MfmaParams p) {
   };
   const int nchunks = p.cin / KC;
   constexpr bool AHEAD = MI * NI <= 4;   // registers to spare for table entries fetched ahead
+  // vector-ALU instructions of the activation per MFMA of an active k-step (8 per element with SiLU, 3 without),
+  // one less than the average so that the tail of a word does not delay the next k-step; the 256-pixel tiles keep
+  // the order as written (spreading measured 0 to -4 % there, +1 to +2 % on the small tiles)
+  constexpr int SPREAD_AVG = (NV * 8 * (ACT == 2 ? 8 : 3) + (SLOTS - SLOTS / 3) * NI - 1) / ((SLOTS - SLOTS / 3) * NI);
+  constexpr int SPREAD = (ACT == 0 || MI * NI > 4) ? -1 : (SPREAD_AVG > 1 ? SPREAD_AVG - 1 : 1);
   f32x4 abv[2];   // table entries of the part being activated and of the next one (sliced activation)
 
   TRACE(0);
@@ -500,11 +519,11 @@ void conv_mfma_kernel(MfmaParams p) {
       };
       // the last chunk activates a harmless reload into the buffer nobody reads: one instruction stream, no
       // control flow inside the pinned schedule
-      mfma_chunk<T, MI, NI, KT, KC, HW_, PS, D, true>(buf, a_off, wrsrc, bcur, bnext, tap_stride, kk_stride, lane16, bq, acc, slice);
+      mfma_chunk<T, MI, NI, KT, KC, HW_, PS, D, true, SPREAD>(buf, a_off, wrsrc, bcur, bnext, tap_stride, kk_stride, lane16, bq, acc, slice);
       TRACE(3 + 4 * c);
     } else {
       auto none = [](auto) {};
-      mfma_chunk<T, MI, NI, KT, KC, HW_, PS, D, false>(buf, a_off, wrsrc, bcur, bnext, tap_stride, kk_stride, lane16, bq, acc, none);
+      mfma_chunk<T, MI, NI, KT, KC, HW_, PS, D, false, -1>(buf, a_off, wrsrc, bcur, bnext, tap_stride, kk_stride, lane16, bq, acc, none);
       TRACE(3 + 4 * c);
       if (more) activate_all(c0n, nbuf);
     }
