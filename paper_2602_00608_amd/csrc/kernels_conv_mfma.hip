@@ -211,10 +211,11 @@ __device__ __forceinline__ void static_for(F&& f) { static_for_impl<N>(f, std::m
 
 // Ring length of the weight-fragment prefetch: it must divide the k-steps of a chunk so that the ring
 // position is the same at every chunk start.
-// It is as long as the register budget of the tile allows (`room`: accumulator tiles per wavefront): the
-// fragments come from the L2, whose latency is several k-steps.
+// It is as long as the register budget of the tile allows (`room`: accumulator tiles per wavefront): the fragments
+// come from the L2, whose latency is several k-steps.  The 256-pixel tiles, at the 256-register limit, take the
+// short ring and spend the registers on the activation-table prefetch instead (measured: +1.5 to 2 %).
 constexpr int prefetch_ring(int steps, int room) {
-  (void)room;
+  if (room > 4 && steps % 3 == 0) return 3;
   if (steps % 6 == 0) return 6;
   return steps % 3 == 0 ? 3 : (steps % 4 == 0 ? 4 : 2);
 }
@@ -464,7 +465,6 @@ void conv_mfma_kernel(MfmaParams p) {
     }
   };
   const int nchunks = p.cin / KC;
-  constexpr bool AHEAD = MI * NI <= 4;   // registers to spare for table entries fetched ahead
   // vector-ALU instructions of the activation per MFMA of an active k-step (8 per element with SiLU, 3 without),
   // one less than the average so that the tail of a word does not delay the next k-step; the 256-pixel tiles keep
   // the order as written (spreading measured 0 to -4 % there, +1 to +2 % on the small tiles)
@@ -494,26 +494,19 @@ void conv_mfma_kernel(MfmaParams p) {
       // Slots FIRST .. SLOTS-1 share the NV*4 words of the next chunk evenly.  All vectors of a thread hold the same
       // channel octet, so the words are taken part by part (word `part` of every vector, then the next part) and
       // the four table entries of the octet are read from LDS once each, one part ahead of their first use: a read
-      // issued right where it is needed would expose the LDS latency in every slot.  (The 256-pixel tiles have no
-      // eight registers to spare for that and read the entry per word.)
+      // issued right where it is needed would expose the LDS latency in every slot.
       auto slice = [&](auto slot_c) {
         constexpr int slot = decltype(slot_c)::value;
         constexpr int FIRST = SLOTS / 3, SPAN = SLOTS - FIRST, NW = NV * 4;
-        if constexpr (AHEAD && slot == FIRST - 1) abv[0] = table_entry(0, c0n);
+        if constexpr (slot == FIRST - 1) abv[0] = table_entry(0, c0n);
         if constexpr (slot >= FIRST) {
           constexpr int w0 = (slot - FIRST) * NW / SPAN, w1 = (slot - FIRST + 1) * NW / SPAN;
           static_for<w1 - w0>([&](auto k_c) {
             constexpr int wi = w0 + decltype(k_c)::value;
-            if constexpr (AHEAD) {
-              constexpr int part = wi / NV, i = wi % NV;
-              if constexpr (i == 0 && part < 3) abv[(part + 1) & 1] = table_entry(part + 1, c0n);
-              raw[i][part] = activate_with(raw[i][part], abv[part & 1]);
-              if constexpr (part == 3) store_vec(i, nbuf);
-            } else {
-              constexpr int i = wi / 4, part = wi % 4;
-              raw[i][part] = activate_word(raw[i][part], i, part, c0n);
-              if constexpr (part == 3) store_vec(i, nbuf);
-            }
+            constexpr int part = wi / NV, i = wi % NV;
+            if constexpr (i == 0 && part < 3) abv[(part + 1) & 1] = table_entry(part + 1, c0n);
+            raw[i][part] = activate_with(raw[i][part], abv[part & 1]);
+            if constexpr (part == 3) store_vec(i, nbuf);
           });
         }
       };
