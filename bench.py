@@ -22,11 +22,11 @@ PEAK = {"mfma": 2516.6, "hbm": 8000.0}   # TFLOP/s dense bf16/f16 MFMA, GB/s HBM
 # frame: counter passes of this same command under rocprofv3, scaled by what the counters read for a plain copy of
 # known size.  Counters cannot be collected from inside this process; the passes are summarised under profiles/.
 PMC_TRAFFIC_MB = {
-    "conv_mfma_kernel<wmdec::f16_t, wmdec::f16_t, 8, 16, 1, 4, 1, 3, 32, 2, false>": (134.6, 33.3),
-    "conv_mfma_kernel<wmdec::f16_t, wmdec::f16_t, 8, 32, 2, 2, 2, 3, 32, 2, false>": (175.8, 89.6),
-    "conv_mfma_kernel<wmdec::f16_t, wmdec::f16_t, 8, 16, 4, 1, 2, 3, 32, 0, true>": (174.3, 96.3),
+    "conv_mfma_kernel<wmdec::f16_t, wmdec::f16_t, 8, 16, 1, 4, 1, 3, 32, 2, false>": (140.7, 33.3),
+    "conv_mfma_kernel<wmdec::f16_t, wmdec::f16_t, 8, 32, 2, 2, 2, 3, 32, 2, false>": (177.0, 89.6),
+    "conv_mfma_kernel<wmdec::f16_t, wmdec::f16_t, 8, 16, 4, 1, 2, 3, 32, 0, true>": (174.2, 96.3),
     "conv_mfma_kernel<wmdec::f16_t, wmdec::f16_t, 8, 32, 2, 2, 2, 1, 64, 0, false>": (179.0, 66.4),
-    "conv_mfma_kernel<wmdec::f16_t, wmdec::f16_t, 8, 16, 2, 2, 2, 3, 32, 2, false>": (35.4, 5.6),
+    "conv_mfma_kernel<wmdec::f16_t, wmdec::f16_t, 8, 16, 2, 2, 2, 3, 32, 2, false>": (35.3, 5.6),
     "flash_attn_kernel": (106.0, 33.3),
 }
 
