@@ -29,11 +29,12 @@ int hip_fail(hipError_t e, const char* what) {
 
 int launch_conv(const ConvArgs& a, hipStream_t s) {
   if (conv_mfma_supported(a)) return launch_conv_mfma(a, s);
+  if (conv_small_cin_supported(a)) return launch_conv_small_cin(a, s);
   return launch_conv_direct(a, s);
 }
 
 const char* conv_kernel_label(const ConvArgs& a) {
-  if (!conv_mfma_supported(a)) return "conv_direct_kernel";
+  if (!conv_mfma_supported(a)) return conv_small_cin_supported(a) ? "conv_small_cin_kernel" : "conv_direct_kernel";
   return conv_mfma_label(a);
 }
 

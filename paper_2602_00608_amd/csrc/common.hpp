@@ -95,6 +95,9 @@ struct ConvArgs {
 
 // kernels_conv_direct.hip: general VALU convolution (any shape, all dtypes).
 int launch_conv_direct(const ConvArgs& a, hipStream_t s);
+// same file: 3x3 convolution with at most 8 input channels, no normalisation / residual, NHWC output (conv_in)
+bool conv_small_cin_supported(const ConvArgs& a);
+int launch_conv_small_cin(const ConvArgs& a, hipStream_t s);
 // kernels_conv_mfma.hip: implicit-GEMM MFMA convolution; returns 1 if the shape
 // is not one it handles (caller falls back to the direct kernel), 0 if launched.
 bool conv_mfma_supported(const ConvArgs& a);

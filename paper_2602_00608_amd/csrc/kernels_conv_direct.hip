@@ -153,7 +153,83 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(DirectParams p) {
   }
 }
 
+// 3x3 convolution with very few input channels (the decoder's conv_in, C_in = 4): far too little contraction for
+// the matrix cores, and the general kernel above spends its time staging.  A thread owns one output channel and
+// keeps that channel's 9 x CI weights in registers (the packed layout stores the first 8 input channels of a
+// (tap, output channel) pair as 16 contiguous bytes); a workgroup walks a row segment of 32 pixels whose
+// three-row halo strip sits in LDS (operands rounded to the operand type, zeros outside the image), so every
+// input value is one broadcast LDS read for 256 output channels.  Bias in the epilogue, NHWC output.
+constexpr int SP = 32;   // pixels per workgroup
+
+template <int CI, typename TW_, typename TO>
+__global__ __launch_bounds__(256) void conv_small_cin_kernel(const void* __restrict__ x, int x_dtype, int x_nchw,
+                                                             const TW_* __restrict__ w, const float* __restrict__ bias,
+                                                             TO* __restrict__ y, int h, int w_out, int cin, int cout) {
+  __shared__ __align__(16) float s_in[3][SP + 2][CI];
+  const int tid = threadIdx.x;
+  const int segs = (w_out + SP - 1) / SP;
+  const int oy = blockIdx.x / segs, x0 = (blockIdx.x % segs) * SP;
+  const int co = blockIdx.y * 256 + tid;
+  const int n = blockIdx.z;
+  for (int i = tid; i < 3 * (SP + 2) * CI; i += 256) {
+    const int c = i % CI, hx = (i / CI) % (SP + 2), hy = i / (CI * (SP + 2));
+    const int gy = oy + hy - 1, gx = x0 + hx - 1;
+    float v = 0.f;
+    if (c < cin && gy >= 0 && gy < h && gx >= 0 && gx < w_out) {
+      const size_t idx = x_nchw ? (((size_t)n * cin + c) * h + gy) * w_out + gx : (((size_t)n * h + gy) * w_out + gx) * cin + c;
+      v = round_through<TW_>(load_as_float(x, x_dtype, idx));
+    }
+    s_in[hy][hx][c] = v;
+  }
+  float wr[9][CI];
+  const int coutb = packed_cout_blocks(cout), cinb = packed_cin_blocks(cin);
+  const int cc = min(co, cout - 1);
+#pragma unroll
+  for (int tap = 0; tap < 9; ++tap) {
+    const TW_* src = w + packed_index(tap, cc, 0, cinb, coutb);   // input channels 0..7 of (tap, cc): 16 contiguous bytes
+#pragma unroll
+    for (int c = 0; c < CI; ++c) wr[tap][c] = to_float(src[c]);
+  }
+  const float bv = bias ? bias[cc] : 0.f;
+  __syncthreads();
+  if (co >= cout) return;
+  TO* yrow = y + (((size_t)n * h + oy) * w_out + x0) * cout + co;
+  const int npx = min(SP, w_out - x0);
+  for (int px = 0; px < npx; ++px) {
+    float acc = bv;
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap)
+#pragma unroll
+      for (int c = 0; c < CI; ++c) acc = fmaf(s_in[tap / 3][px + tap % 3][c], wr[tap][c], acc);
+    yrow[(size_t)px * cout] = from_float<TO>(acc);
+  }
+}
+
+template <int CI, typename TW_>
+int launch_small_cin_t(const ConvArgs& a, hipStream_t s) {
+  const int segs = (a.w + SP - 1) / SP;
+  dim3 grid((unsigned)(segs * a.h), (unsigned)((a.cout + 255) / 256), (unsigned)a.n);
+  switch (a.y_dtype) {
+    case WMDEC_F32: hipLaunchKernelGGL((conv_small_cin_kernel<CI, TW_, float>), grid, dim3(256), 0, s, a.x, a.x_dtype, a.x_nchw, (const TW_*)a.wt, a.bias, (float*)a.y, a.h, a.w, a.cin, a.cout); break;
+    case WMDEC_BF16: hipLaunchKernelGGL((conv_small_cin_kernel<CI, TW_, bf16_t>), grid, dim3(256), 0, s, a.x, a.x_dtype, a.x_nchw, (const TW_*)a.wt, a.bias, (bf16_t*)a.y, a.h, a.w, a.cin, a.cout); break;
+    default: hipLaunchKernelGGL((conv_small_cin_kernel<CI, TW_, f16_t>), grid, dim3(256), 0, s, a.x, a.x_dtype, a.x_nchw, (const TW_*)a.wt, a.bias, (f16_t*)a.y, a.h, a.w, a.cin, a.cout); break;
+  }
+  WMDEC_HIP(hipGetLastError());
+  return WMDEC_OK;
+}
+
 }  // namespace
+
+bool conv_small_cin_supported(const ConvArgs& a) {
+  return a.ksize == 3 && !a.upsample && a.cin <= 8 && !a.mean && !a.groups_norm && !a.res && !a.y_nchw && is_16bit(a.op_dtype) &&
+         a.stats_ws == nullptr;
+}
+
+int launch_conv_small_cin(const ConvArgs& a, hipStream_t s) {
+  if (a.cin <= 4)
+    return a.op_dtype == WMDEC_BF16 ? launch_small_cin_t<4, bf16_t>(a, s) : launch_small_cin_t<4, f16_t>(a, s);
+  return a.op_dtype == WMDEC_BF16 ? launch_small_cin_t<8, bf16_t>(a, s) : launch_small_cin_t<8, f16_t>(a, s);
+}
 
 int launch_conv_direct(const ConvArgs& a, hipStream_t s) {
   DirectParams p;

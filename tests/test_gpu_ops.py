@@ -145,6 +145,8 @@ CONV_CASES = [
     ("f16", "f16", 1, 256, 128, 17, 33, True, True, True, False),
     ("f16", "f32", 1, 128, 3, 24, 31, True, True, True, False),      # conv_out shape class
     ("bf16", "f32", 1, 4, 64, 12, 18, False, False, True, False),    # conv_in shape class
+    ("f16", "f16", 2, 4, 512, 9, 70, False, False, True, False),     # conv_in: two channel blocks, three row segments
+    ("f16", "f16", 1, 7, 100, 5, 33, False, False, False, False),    # few input channels, ragged channel block
     ("bf16", "f32", 1, 512, 512, 15, 23, True, True, True, True),
     ("f16", "f32", 1, 32, 32, 64, 3, True, True, True, True),        # narrow image
 ]
