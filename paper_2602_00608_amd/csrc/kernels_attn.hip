@@ -78,7 +78,7 @@ __global__ __launch_bounds__(NT) void flash_attn_kernel(const T* __restrict__ q,
   float m_run = -INFINITY, l_run = 0.f;
 
   // staging: thread -> KV vectors of the K tile (row r, 16-byte column c) and of the V^T tile (row d, 8 keys)
-  u32x4 pre[KV];
+  u32x4 pre[KV], prev[KV];   // next K tile, next V^T tile: both fetched at the start of a key block
   auto load_k = [&](int kb) {
 #pragma unroll
     for (int i = 0; i < KV; ++i) {
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(NT) void flash_attn_kernel(const T* __restrict__ q,
 #pragma unroll
     for (int i = 0; i < KV; ++i) {
       const int v = tid + i * NT, r = v / (KB / 8), c = v % (KB / 8);
-      pre[i] = reinterpret_cast<const u32x4*>(vt + (size_t)r * t_pad + min(kb, t_pad - KB) + c * 8)[0];
+      prev[i] = reinterpret_cast<const u32x4*>(vt + (size_t)r * t_pad + min(kb, t_pad - KB) + c * 8)[0];
     }
   };
   auto store_v = [&](int kb) {   // keys >= t are zeroed: their probability is 0 but 0 * garbage could be NaN
@@ -105,7 +105,7 @@ __global__ __launch_bounds__(NT) void flash_attn_kernel(const T* __restrict__ q,
     for (int i = 0; i < KV; ++i) {
       const int v = tid + i * NT, r = v / (KB / 8), c = v % (KB / 8);
       const int key = kb + c * 8;
-      uint32_t w[4] = {pre[i].x, pre[i].y, pre[i].z, pre[i].w};
+      uint32_t w[4] = {prev[i].x, prev[i].y, prev[i].z, prev[i].w};
       if (key + 8 > t) {
 #pragma unroll
         for (int e = 0; e < 8; ++e)
@@ -124,15 +124,32 @@ __global__ __launch_bounds__(NT) void flash_attn_kernel(const T* __restrict__ q,
   for (int kb = kb_begin; kb < kb_end; kb += KB) {
     const int kn = min(kb + KB, kb_end - KB);   // next block (the last iteration reloads its own: harmless)
     load_k(kn);
+    load_v(kn);
     if (wave < SW) {
       // S^T tiles: keys kb + 16*tile + 4*lg + r, query qb0 + 16*wave + lq
+      // K fragments are read from LDS PF contraction steps ahead of the MFMAs that consume them; the scheduling
+      // barriers keep that distance (left alone, the compiler sinks each read to its use and every step pays
+      // the LDS latency)
       f32x4 s0 = f32x4{0.f, 0.f, 0.f, 0.f}, s1 = s0;
+      constexpr int PF = 3;
+      u32x4 ka[PF][2];
+      const T* krow0 = s_k + lq * K_LD + lg * 8;
+      const T* krow1 = krow0 + 16 * K_LD;
+#pragma unroll
+      for (int st = 0; st < PF; ++st) {
+        ka[st][0] = *reinterpret_cast<const u32x4*>(krow0 + st * 32);
+        ka[st][1] = *reinterpret_cast<const u32x4*>(krow1 + st * 32);
+      }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int st = 0; st < D / 32; ++st) {
-        const u32x4 a0 = *reinterpret_cast<const u32x4*>(s_k + lq * K_LD + st * 32 + lg * 8);
-        const u32x4 a1 = *reinterpret_cast<const u32x4*>(s_k + (16 + lq) * K_LD + st * 32 + lg * 8);
-        s0 = Mma<T>::m16(a0, qf[st], s0);
-        s1 = Mma<T>::m16(a1, qf[st], s1);
+        s0 = Mma<T>::m16(ka[st % PF][0], qf[st], s0);
+        s1 = Mma<T>::m16(ka[st % PF][1], qf[st], s1);
+        if (st + PF < D / 32) {
+          ka[st % PF][0] = *reinterpret_cast<const u32x4*>(krow0 + (st + PF) * 32);
+          ka[st % PF][1] = *reinterpret_cast<const u32x4*>(krow1 + (st + PF) * 32);
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
       float sv[8];
 #pragma unroll
@@ -159,7 +176,6 @@ __global__ __launch_bounds__(NT) void flash_attn_kernel(const T* __restrict__ q,
     }
     __syncthreads();            // probabilities and rescale factors visible; every wavefront is done with the K tile
     store_k();                  // next K tile
-    load_v(kn);
     {
       const float al0 = s_alpha[l32], al1 = s_alpha[32 + l32];
       if (__any(al0 != 1.0f || al1 != 1.0f)) {
