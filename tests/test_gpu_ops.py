@@ -28,6 +28,9 @@ def rng(seed):
     ("f16", 3, 24, 9, 11, 3),        # general path, 16 bit
     ("f32", 1, 32, 1, 1, 32),        # one element per group: variance 0
     ("bf16", 1, 128, 480, 720, 32),  # workload 3 size
+    ("f16", 70, 64, 3, 5, 32),       # more samples than one 256-byte block of ticket counters holds
+    ("f16", 2, 1024, 4, 6, 32),      # widest tensor of the single-launch path (one pixel per sweep)
+    ("bf16", 1, 2048, 3, 3, 32),     # wider than that: general path
 ])
 def test_gn_stats(dtype, n, c, h, w, groups):
     x = G.stored(rng(1).standard_normal((n, c, h, w)) * 1.7 + 0.6, dtype)
