@@ -353,19 +353,6 @@ void conv_mfma_kernel(MfmaParams p) {
   const int h_in = p.upsample ? p.h >> 1 : p.h, w_in = p.upsample ? p.w_out >> 1 : p.w_out;
   const int h_t = PH ? h_in : p.h, w_t = PH ? w_in : p.w_out;   // the grid the tiles live on
 
-  // per-channel scale/shift table: a = gamma*rstd, b = beta - mean*a.  With SiLU the table holds -log2(e) * (a, b):
-  // the staged value is u = -log2(e) * t, from which silu(t) = t / (1 + 2^u) = u / (-log2(e) - log2(e) * 2^u) takes
-  // one exp2, one fma, one reciprocal and one multiply
-  if constexpr (ACT > 0) {
-    const int cpg = p.cin / p.groups;
-    const float k = ACT == 2 ? -1.4426950408889634f : 1.0f;
-    for (int c = tid; c < p.cin; c += NT) {
-      const int g = c / cpg;
-      const float a = p.gamma[c] * p.rstd[n * p.groups + g];
-      s_ab[c] = make_float2(k * a, k * (p.beta[c] - p.mean[n * p.groups + g] * a));
-    }
-  }
-
   f32x16 acc[MI][NI];
 #pragma unroll
   for (int i = 0; i < MI; ++i)
@@ -477,6 +464,19 @@ void conv_mfma_kernel(MfmaParams p) {
   if (p.trace && tid == 0) p.trace[(size_t)blockIdx.x * 64 + 60] = clock64();
 #endif
   issue(0);
+  // (built behind the first chunk's loads, so that its own global loads overlap them)
+  // per-channel scale/shift table: a = gamma*rstd, b = beta - mean*a.  With SiLU the table holds -log2(e) * (a, b):
+  // the staged value is u = -log2(e) * t, from which silu(t) = t / (1 + 2^u) = u / (-log2(e) - log2(e) * 2^u) takes
+  // one exp2, one fma, one reciprocal and one multiply
+  if constexpr (ACT > 0) {
+    const int cpg = p.cin / p.groups;
+    const float k = ACT == 2 ? -1.4426950408889634f : 1.0f;
+    for (int c = tid; c < p.cin; c += NT) {
+      const int g = c / cpg;
+      const float a = p.gamma[c] * p.rstd[n * p.groups + g];
+      s_ab[c] = make_float2(k * a, k * (p.beta[c] - p.mean[n * p.groups + g] * a));
+    }
+  }
   __syncthreads();            // scale/shift table complete
   activate_all(0, s_a);
   issue(1);
