@@ -4,19 +4,22 @@
 // One workgroup (4 wavefronts) owns a TH x TW patch of output pixels and TN
 // output channels.  Per chunk of KC input channels it stages the patch plus its
 // one-pixel halo into LDS -- GroupNorm scale/shift and SiLU are applied there,
-// once per element, positions outside the image become zeros, and a folded
-// nearest-2x upsample is just a different source address -- and then sweeps the
-// nine taps over that tile: the A operand of every MFMA is a 16-byte LDS read
-// at a tap-dependent constant offset, the B operand (weights) comes straight
-// from global memory, where the packed layout stores every 32(co) x 16(ci)
-// fragment as 1 KiB in lane order, so a wavefront's load is one contiguous KiB.
-// Accumulators stay in registers for the whole K loop; bias, residual and the
-// single rounding to the storage type happen in the epilogue.
-// The staged tile is double-buffered: the global loads of the next chunk are
-// issued before the MFMA sweep of the current one and activated into the other
-// buffer after it, with one workgroup barrier per chunk.  Two workgroups fit on
-// a compute unit (registers <= 256, LDS < 80 KiB), so one activates while the
-// other multiplies.
+// once per element, and positions outside the image are zeros -- and then sweeps
+// the nine taps over that tile: the A operand of every MFMA is a 16-byte LDS read
+// at a tap-dependent constant offset, the B operand (weights) is loaded straight
+// from the L2-resident packed weights, where every 32(co) x 16(ci) fragment is
+// 1 KiB in lane order, so a wavefront's load is one contiguous KiB.
+// Accumulators stay in registers for the whole K loop; bias, residual, the single
+// rounding to the storage type and the GroupNorm moments of the output happen in
+// the epilogue.
+// The staged tile is double-buffered: the raw vectors of chunk c+2 are loaded
+// right after the sweep of chunk c, and chunk c+1 is activated and stored into
+// the other buffer in compile-time slots inside the sweep of chunk c, with one
+// workgroup barrier per chunk.  Two or three workgroups fit on a compute unit, so
+// the prologue and epilogue of one overlap the sweeps of the others.
+// A nearest-2x upsample in front of the convolution is either folded into the
+// staging address (bf16) or, in f16, removed algebraically: the phase mode
+// computes each of the four output phases as a 2x2 convolution on the input grid.
 #include <stdio.h>
 #include <stdlib.h>
 
