@@ -1,13 +1,15 @@
 // GroupNorm statistics: a streaming read of an NHWC tensor producing, per
 // (sample, group), the mean and 1/sqrt(biased variance + eps).
 //
-// Stage 1 (gn_partial_*): the pixels of a sample are cut into `chunks` slabs;
-// one workgroup reads a slab with 16-byte vector loads (every thread keeps a
-// fixed set of channels), accumulates shifted sums in fp32 (shift = the first
-// value a thread sees per channel, so that E[x^2]-E[x]^2 never cancels), and
-// writes one (count, mean, M2) triple per group.  Stage 2 (gn_finalize) merges
-// the triples of a group with the pairwise update of Chan et al. in a fixed
-// order, so the result does not depend on scheduling.
+// The pixels of a sample are cut into slabs; a workgroup reads its slab with
+// 16-byte vector loads (every thread keeps a fixed set of channels), accumulates
+// shifted sums in fp32 (so that E[d^2]-E[d]^2 never cancels) and produces one
+// (count, mean, M2) triple per group.  Triples are merged with the pairwise
+// update of Chan et al. in a fixed order, so the result does not depend on
+// scheduling.  Channel counts that fit the vector layout take the single-launch
+// kernel gn_stats_vec, whose last workgroup per sample does the merge; everything
+// else takes gn_partial_any followed by gn_finalize, which also merges the
+// moments a convolution emitted from its epilogue.
 #include "moments.hpp"
 
 namespace wmdec {
