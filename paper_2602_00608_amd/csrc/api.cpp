@@ -152,7 +152,7 @@ struct Builder {
     Step s; s.kind = Step::STATS; s.src = src; s.h = h; s.w = w; s.cin = c;
     s.bytes = (double)h * w * c * dtype_size(d.cfg.act_dtype);
     d.steps.push_back(s);
-    d.launches += 2;
+    d.launches += gn_stats_num_launches(d.cfg.act_dtype, h, w, c, d.cfg.groups);
   }
   // call right after pushing a CONV step: accounts its work on the pushed copy
   void count_conv(const Step&) {
@@ -226,7 +226,7 @@ static void fuse_stats_into_producers(wmdec_decoder& d) {
     d.steps[j].emit_stats = 1;
     st.from_producer = 1;
     st.bytes = 0.0;          // no tensor traffic left in this step
-    d.launches -= 1;
+    d.launches -= gn_stats_num_launches(d.cfg.act_dtype, st.h, st.w, st.cin, d.cfg.groups) - 1;   // one merge launch remains
   }
 }
 

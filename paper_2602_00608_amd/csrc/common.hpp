@@ -114,6 +114,7 @@ const char* conv_kernel_label(const ConvArgs& a);
 // moments: scratch of at least gn_stats_moments_bytes(n, groups) bytes
 size_t gn_stats_ticket_bytes(int n);
 size_t gn_stats_moments_bytes(int n, int groups);
+int gn_stats_num_launches(int x_dtype, int h, int w, int c, int groups);   // 1: single-launch kernel, 2: partial + merge
 int launch_gn_stats(const void* x, int x_dtype, int n, int h, int w, int c, int groups, float eps,
                     float* mean, float* rstd, unsigned* ticket, void* moments, size_t moments_bytes, hipStream_t s);
 

@@ -264,6 +264,10 @@ size_t gn_stats_moments_bytes(int n, int groups) {
   return (size_t)n * groups * 2048 * sizeof(Moments);
 }
 
+int gn_stats_num_launches(int x_dtype, int h, int w, int c, int groups) {
+  return make_plan(x_dtype, 1, h, w, c, groups).vec ? 1 : 2;
+}
+
 int launch_gn_stats(const void* x, int x_dtype, int n, int h, int w, int c, int groups, float eps,
                     float* mean, float* rstd, unsigned* ticket, void* moments, size_t moments_bytes, hipStream_t s) {
   const Plan p = make_plan(x_dtype, n, h, w, c, groups);
