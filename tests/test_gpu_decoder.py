@@ -177,6 +177,44 @@ def test_time_step_repeats_a_step_without_changing_the_frame():
     dec.close()
 
 
+def test_decoder_run_replays_from_a_captured_graph():
+    """decoder_run enqueues only kernels (no memset nodes, no allocation, no synchronisation), so a caller can
+    capture it in a HIP graph: every replay, with eager runs and synchronisations in between, must reproduce
+    the eager frame bit for bit."""
+    cfg = small_cfg(wmdec.F16)
+    spec = synth.decoder_weight_spec(level_channels=(512, 128, 64, 32), resblocks_per_level=2)
+    weights = synth.draw_params(spec, synth.weight_seed(9), random_affine=True)
+    z = synth.latent_sequence(workload=9, frames=2, h=7, w=9)
+    dec = wmdec.Decoder(cfg)
+    packed = torch.empty(dec.packed_bytes(), dtype=torch.uint8, device="cuda")
+    dec.pack_weights(make_blob(dec, weights), packed)
+    ws = torch.empty(dec.workspace_bytes(2), dtype=torch.uint8, device="cuda")
+    dec.set_workspace(ws)
+    zd = torch.from_numpy(synth.bf16_bits(z).view(np.int16)).view(torch.bfloat16).cuda()
+    out = torch.empty((2, cfg.out_c, 56, 72), dtype=torch.float32, device="cuda")
+    dec.run(zd, packed, out)            # eager: also the one-time set-up (kernel attributes, ticket counters)
+    torch.cuda.synchronize()
+    eager = out.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        dec.run(zd, packed, out)
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        dec.run(zd, packed, out)
+    for _ in range(3):
+        out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager)
+        dec.run(zd, packed, out)        # eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager)
+    del graph
+    dec.close()
+
+
 def test_decoder_full_size_f16(workload4):
     """Workload 4: z[1,4,60,90] -> [1,3,480,720], full decoder, against the fp64 oracle."""
     weights, z, want = workload4
