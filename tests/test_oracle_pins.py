@@ -2,6 +2,7 @@
 not the oracle itself -- brute force in pure Python, closed forms, invariants,
 or an independent library routine (scipy / numpy)."""
 import itertools
+import os
 import math
 
 import numpy as np
@@ -381,3 +382,18 @@ def test_decoder_reduced_size_independent_route():
 def test_rel_err_metric():
     want = np.array([3.0, -4.0])
     assert abs(ref.rel_err(want + np.array([0.0, 0.5]), want) - 0.5 / math.sqrt(12.5)) < 1e-15
+
+
+def test_reduced_decoder_matches_stored_oracle_values():
+    """Drift guard: the oracle's reduced decoder against values it wrote earlier (tests/golden/make_golden.py).
+    Not a pin by itself -- the pins are the tests above -- but any change to the oracle's arithmetic shows here."""
+    import importlib.util
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "golden", "make_golden.py"))
+    mg = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mg)
+    shape, idx, vals, rms = mg.reduced_decoder_samples()
+    rows = [l.split() for l in open(os.path.join(here, "golden", "reduced_decoder_f64.txt")) if not l.startswith("#")]
+    want_idx = np.array([int(r[0]) for r in rows]); want = np.array([float(r[1]) for r in rows])
+    assert shape == (1, 3, 56, 72) and np.array_equal(idx, want_idx)
+    assert np.max(np.abs(vals - want)) <= 1e-9 * rms
