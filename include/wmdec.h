@@ -211,8 +211,11 @@ int decoder_set_workspace(wmdec_decoder* dec, void* workspace, size_t bytes);
 
 /* latent: [batch,latent_c,h,w] NCHW, BF16.  packed: from decoder_pack_weights.
  * out: [batch,out_c,8h,8w] NCHW, F32.  1 <= batch <= max_batch.  Enqueues the
- * whole graph on `stream`; no host synchronisation.  Calls that share one
- * decoder (hence one workspace) must be ordered on the same stream. */
+ * whole graph on `stream`; no host synchronisation, no allocation, kernels
+ * only (after the first call on a workspace, which also sets kernel attributes
+ * and zeroes the statistics counters, the call may be captured in a HIP graph).
+ * Calls that share one decoder (hence one workspace) must be ordered on the
+ * same stream. */
 int decoder_run(wmdec_decoder* dec, const void* latent, const void* packed, void* out, int batch,
                 void* stream);
 
