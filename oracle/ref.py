@@ -178,6 +178,24 @@ def decoder(z, weights, level_channels=(512, 512, 256, 128), resblocks_per_level
     return conv2d(x, weights["conv_out.w"], weights["conv_out.b"])
 
 
+def latent_extrapolate(z_prev, v_prev, lam):
+    """Hit branch of the latent-extrapolation algorithm (Sec. IV-C, Alg. 2): the world model is skipped and the
+    next latent is the first-order Taylor step of that section, z_t = z_{t-1} + lambda * v_{t-1}, with the motion
+    vector v_{t-1} = z_{t-1} - z_{t-2} standing in for dz/dt."""
+    return _f64(z_prev) + float(lam) * _f64(v_prev)
+
+
+def extrapolated_latents(z_prev, v_prev, lam, hits):
+    """`hits` consecutive hit steps of Alg. 2.  The motion vector is only updated on a miss, so every step adds the
+    same lambda * v to the latent the previous step produced.  Returns [hits, ...]: the latent of every step."""
+    z = _f64(z_prev)
+    out = []
+    for _ in range(int(hits)):
+        z = latent_extrapolate(z, v_prev, lam)
+        out.append(z)
+    return np.stack(out) if out else np.empty((0,) + z.shape)
+
+
 def rel_err(got, want):
     """max|got-want| / rms(want): the comparison metric of every parity test."""
     want = np.asarray(want, dtype=np.float64)

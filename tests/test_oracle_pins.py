@@ -379,6 +379,36 @@ def test_decoder_reduced_size_independent_route():
     np.testing.assert_allclose(one, got[1:2], rtol=0, atol=1e-12)
 
 
+def test_latent_extrapolation_pins():
+    """Alg. 2, hit branch (Sec. IV-C).  A trajectory that really is linear in time, z(t) = a + t*d, is reproduced
+    exactly by the scheme with lambda = 1 and v = z(t-1) - z(t-2) (catches a flipped sign, a wrong operand, a
+    motion vector that is updated on hits); lambda = 0 is the identity; the step is linear in lambda and in v; k
+    hits equal the closed form z + k*lambda*v; a hand loop over a tiny latent."""
+    r = np.random.default_rng(77)
+    a, d = r.standard_normal((4, 5, 6)), r.standard_normal((4, 5, 6))
+    traj = lambda t: a + t * d
+    z2, z1 = traj(5.0), traj(6.0)
+    got = ref.extrapolated_latents(z1, z1 - z2, 1.0, 3)
+    for j in range(3):
+        assert np.allclose(got[j], traj(7.0 + j), rtol=0, atol=1e-12)
+    z, v = r.standard_normal((2, 3, 3)), r.standard_normal((2, 3, 3))
+    assert np.array_equal(ref.latent_extrapolate(z, v, 0.0), z)
+    assert np.allclose(ref.latent_extrapolate(z, v, 0.7) - z, 0.7 * v, atol=1e-15)
+    assert np.allclose(ref.latent_extrapolate(z, 2.0 * v, 0.35), ref.latent_extrapolate(z, v, 0.7), atol=1e-15)
+    k = ref.extrapolated_latents(z, v, 0.3, 4)
+    assert k.shape == (4, 2, 3, 3) and np.allclose(k[3], z + 4 * 0.3 * v, atol=1e-14)
+    assert ref.extrapolated_latents(z, v, 0.3, 0).shape == (0, 2, 3, 3)
+    want = np.empty_like(z)
+    for c in range(2):
+        for y in range(3):
+            for x in range(3):
+                want[c, y, x] = z[c, y, x] + 0.3 * v[c, y, x]
+    assert np.array_equal(ref.latent_extrapolate(z, v, 0.3), want)
+    # extrapolating halfway (lambda = 1/2) twice lands where one full step does
+    half = ref.extrapolated_latents(z, v, 0.5, 2)
+    assert np.allclose(half[1], ref.latent_extrapolate(z, v, 1.0), atol=1e-15)
+
+
 def test_rel_err_metric():
     want = np.array([3.0, -4.0])
     assert abs(ref.rel_err(want + np.array([0.0, 0.5]), want) - 0.5 / math.sqrt(12.5)) < 1e-15
