@@ -99,9 +99,36 @@ int wmdec_gn_silu_conv3x3(const void* x, int act_dtype, const float* mean, const
                           const void* w_packed, const float* bias, const void* residual,
                           void* y, int y_dtype, int n, int h, int w, int cin, int cout, void* stream);
 
-/* 1x1 convolution (a GEMM over pixels) with the same optional normalise-on-load,
- * bias and residual; used for the attention projections and the channel-changing
- * ResBlock shortcut.  w_packed: packed with k = 1. */
+/* The same convolution, which in addition returns the GroupNorm statistics of
+ * its own output y, so that the next normalisation needs no statistics pass
+ * and y is not read again (the "one read, one write" accounting of Eq. 9
+ * applied to the Conv2d -> GroupNorm pair of Sec. IV-B-1):
+ *   mean_out[n*out_groups+g], rstd_out[...] = mean and 1/sqrt(biased variance
+ *   + out_eps) of y[n,:,:,g*cout/out_groups .. (g+1)*cout/out_groups), taken
+ * over the values as stored in y (after the rounding to y_dtype), i.e. what
+ * wmdec_gn_stats would return for y up to fp32 summation order.  Every
+ * workgroup writes per-group partial moments of its tile to `workspace`
+ * (wmdec_conv_stats_workspace_bytes(...) bytes, no initialisation needed); a
+ * second small launch merges them in a fixed order.
+ * Only shapes the matrix-core kernel takes can emit moments: 16-bit act_dtype,
+ * cin % 32 == 0, cout % 64 == 0, cout/out_groups a power of two <= 32;
+ * otherwise WMDEC_ERR_UNSUPPORTED (the workspace query then returns 0). */
+size_t wmdec_conv_stats_workspace_bytes(int act_dtype, int y_dtype, int n, int h, int w, int cin,
+                                        int cout, int out_groups);
+int wmdec_gn_silu_conv3x3_stats(const void* x, int act_dtype, const float* mean, const float* rstd,
+                                const float* gamma, const float* beta, int groups, int apply_silu,
+                                const void* w_packed, const float* bias, const void* residual,
+                                void* y, int y_dtype, int n, int h, int w, int cin, int cout,
+                                int out_groups, float out_eps, float* mean_out, float* rstd_out,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/* 1x1 convolution (a GEMM over pixels; the workload's attention projections
+ * q, k, v, proj and the 1x1 shortcut of a channel-changing ResBlock -- the
+ * "plus a residual" of the ResBlock when C_in != C_out) with the same optional
+ * normalise-on-load, bias and residual:
+ *   y[n,p,co] = bias[co] + sum_ci W[co,ci] * u[n,p,ci] (+ residual),
+ * u as for the 3x3 form.  A Conv2d of Sec. IV-B-1 with k = 1.
+ * w_packed: packed with k = 1. */
 int wmdec_gn_conv1x1(const void* x, int act_dtype, const float* mean, const float* rstd,
                      const float* gamma, const float* beta, int groups, int apply_silu,
                      const void* w_packed, const float* bias, const void* residual,
@@ -127,23 +154,32 @@ int wmdec_upsample2x_conv3x3(const void* x, int act_dtype, const void* w_packed,
                              void* y, int y_dtype, int n, int h_in, int w_in, int cin, int cout,
                              void* stream);
 
-/* Stand-alone nearest-neighbour 2x upsample, y[n,oy,ox,c] = x[n,oy>>1,ox>>1,c];
- * bit-exact copy of elements of `dtype`. */
+/* Stand-alone nearest-neighbour 2x upsample (the Upsample operator of
+ * Sec. IV-B-1 on its own, as the unfused graph of Eq. 8 would run it; the
+ * workload's upsample stage, x[1,256,120,180] -> [1,256,240,360]):
+ *   y[n,oy,ox,c] = x[n,oy>>1,ox>>1,c];  bit-exact copy of elements of `dtype`.
+ * Reads x once, writes 4x its size; bounded by HBM bandwidth. */
 int wmdec_upsample2x_nearest(const void* x, void* y, int dtype, int n, int h_in, int w_in, int c,
                              void* stream);
 
 /* ------------------------------------------------------------------------
- * Layout / type conversion between the logical NCHW order and the library's
- * NHWC order: dst = convert(src) element by element (round to nearest even
- * when narrowing). */
+ * Layout / type conversion between the logical NCHW order (B x C x H x W, the
+ * order Sec. IV-A writes feature maps in) and the library's NHWC order:
+ * dst = convert(src) element by element (round to nearest even when
+ * narrowing).  Not on the decoder path (decoder_run reads and writes NCHW at
+ * its two ends itself); for callers of the per-operator entry points. */
 int wmdec_nchw_to_nhwc(const void* src, int src_dtype, void* dst, int dst_dtype,
                        int n, int c, int h, int w, void* stream);
 int wmdec_nhwc_to_nchw(const void* src, int src_dtype, void* dst, int dst_dtype,
                        int n, int c, int h, int w, void* stream);
 
 /* ------------------------------------------------------------------------
- * Mid-block single-head self-attention with residual (flash-style, the score
- * matrix is never materialised):
+ * Mid-block single-head self-attention with residual over the h*w tokens of
+ * the 60x90 feature map (the workload's "single-head self-attention over 5400
+ * tokens, d = 512, GroupNorm before QKV"; the paper names no attention in its
+ * decoder and only cites flash-style kernels as prior art, Sec. II).  The
+ * score matrix is never materialised, in the spirit of Eq. 9: q, k, v are
+ * read once per key block, the output written once:
  *   hn = gamma*(x-mean)*rstd+beta (no SiLU);  [q|k|v] = Wqkv hn + bqkv;
  *   o = softmax_rows(q k^T / sqrt(c)) v;  y = x + Wo o + bo.
  * Tokens are the h*w pixels of one sample.  x, y: [n,h,w,c] of act_dtype
@@ -178,9 +214,15 @@ typedef struct {
   int out_c;                        /* 3 */
   int act_dtype;                    /* WMDEC_BF16 or WMDEC_F16: storage of activations and MFMA operand type */
   int max_batch;                    /* largest batch decoder_run will be given */
+  int latent_dtype;                 /* storage type of the latent handed to decoder_run: WMDEC_BF16 (the workloads),
+                                       WMDEC_F16 or WMDEC_F32 */
+  int separate_stats_pass;          /* 0: a GroupNorm takes its statistics from the epilogue of the convolution that
+                                       produced its input (no extra read of the tensor); 1: every GroupNorm runs the
+                                       streaming statistics pass (wmdec_gn_stats) -- the graph before that fusion */
 } wmdec_decoder_config;
 
-/* Fills *cfg with the 720x480 decoder above (act_dtype = WMDEC_F16, max_batch = 4). */
+/* Fills *cfg with the 720x480 decoder above (act_dtype = WMDEC_F16, max_batch = 4,
+ * latent_dtype = WMDEC_BF16, separate_stats_pass = 0). */
 void decoder_default_config(wmdec_decoder_config* cfg);
 
 /* Validates cfg and builds the host-side plan.  Allocates no device memory. */
@@ -209,7 +251,7 @@ int decoder_pack_weights(const wmdec_decoder* dec, const void* weights, void* pa
 size_t decoder_workspace_bytes(const wmdec_decoder* dec, int batch);
 int decoder_set_workspace(wmdec_decoder* dec, void* workspace, size_t bytes);
 
-/* latent: [batch,latent_c,h,w] NCHW, BF16.  packed: from decoder_pack_weights.
+/* latent: [batch,latent_c,h,w] NCHW of cfg.latent_dtype.  packed: from decoder_pack_weights.
  * out: [batch,out_c,8h,8w] NCHW, F32.  1 <= batch <= max_batch.  Enqueues the
  * whole graph on `stream`; no host synchronisation, no allocation, kernels
  * only (after the first call on a workspace, which also sets kernel attributes
@@ -219,38 +261,42 @@ int decoder_set_workspace(wmdec_decoder* dec, void* workspace, size_t bytes);
 int decoder_run(wmdec_decoder* dec, const void* latent, const void* packed, void* out, int batch,
                 void* stream);
 
-/* Number of kernel launches one decoder_run enqueues, and the algorithmic
- * FLOP count (2*k*k*cin*cout per output pixel of every convolution plus
- * 4*T*T*c per attention) of one frame. */
+/* ------------------------------------------------------------------------
+ * Latent extrapolation in front of the decoder (Sec. IV-C, Alg. 2, hit
+ * branch: when the action is stable the world model is skipped and
+ *   z_t = z_{t-1} + lambda * v_{t-1},   I_t = VAE_Decode(z_t),
+ * with v the motion vector z_{t-1} - z_{t-2}; on consecutive hits v is not
+ * updated, so the j-th skipped frame decodes z_{t-1} + (j+1)*lambda*v).
+ *
+ * decoder_run_extrapolated decodes `batch` such frames in one graph: frame j
+ * (j = 0..batch-1) is VAE_Decode(z_prev + (j+1)*lambda*v_prev).  The sum is
+ * formed where conv_in stages its input (one fp32 fused multiply-add of the
+ * stored values, one rounding to the operand type), so the extrapolated
+ * latents never exist in memory.  z_prev, v_prev: ONE latent each,
+ * [latent_c,h,w] NCHW of cfg.latent_dtype.  Everything else as decoder_run.
+ *
+ * wmdec_latent_extrapolate materialises one extrapolated latent (the state a
+ * caller carries to the next step of Alg. 2):
+ *   z_out[i] = fma((float)steps * lambda, v_prev[i], z_prev[i])  (fp32), rounded
+ * once to out_dtype.  With out_dtype = WMDEC_F32 and a decoder whose
+ * latent_dtype is WMDEC_F32, decoder_run(z_out) reproduces frame steps-1 of
+ * decoder_run_extrapolated bit for bit.  z_prev, v_prev: `count` elements of
+ * `dtype`; z_out: `count` elements of out_dtype; may alias z_prev if the
+ * types have the same size. */
+int decoder_run_extrapolated(wmdec_decoder* dec, const void* z_prev, const void* v_prev, float lambda,
+                             const void* packed, void* out, int batch, void* stream);
+int wmdec_latent_extrapolate(const void* z_prev, const void* v_prev, int dtype, float lambda, int steps,
+                             void* z_out, int out_dtype, size_t count, void* stream);
+
+/* Number of kernel launches one decoder_run enqueues, and the FLOP count of
+ * one frame: 2*k*k*cin*cout per output pixel of every convolution plus
+ * 4*T*T*c for the attention -- except that an upsampling convolution
+ * evaluated per output phase (see wmdec_upsample2x_conv3x3) counts the 2x2
+ * taps it executes, 4/9 of the nine-tap figure.  decoder_dense_flops_per_frame
+ * is the nine-tap figure throughout: what the unfused graph would execute. */
 int decoder_num_launches(const wmdec_decoder* dec);
 double decoder_flops_per_frame(const wmdec_decoder* dec);
-
-/* Per-step timing for measurement.  With profiling enabled decoder_run records
- * a HIP event on `stream` before the first and after every step of the graph
- * (a step = one GroupNorm statistics pass, one convolution, the V transpose or
- * the attention core).  decoder_step_info gives, for step `index`, the name of
- * the kernel that executes it (for convolutions the template instantiation as
- * a profiler prints it; the string is valid until the thread's next call) and
- * its algorithmic FLOPs and HBM bytes per frame (every input, residual, output
- * and weight tensor counted once: the Eq. 9 accounting).  decoder_step_times
- * waits for the last profiled decoder_run and returns the elapsed milliseconds
- * of each step (count = decoder_num_steps); these intervals include the event
- * records themselves, several microseconds per step.
- * decoder_time_step measures one step without that overhead: after a
- * decoder_run with the same arguments has filled the workspace, it enqueues
- * step `step` `reps` times back to back between two HIP events on `stream`,
- * waits, and returns the mean milliseconds per launch.  The step runs on what
- * the workspace holds; steps timed in plan order see the tensors of a real
- * run, except that the second convolution of a channel-changing ResBlock
- * accumulates onto its shortcut in place, once per repetition.  The timing
- * does not depend on the values; call decoder_run again before using the
- * frame or the workspace tensors. */
-int decoder_set_profiling(wmdec_decoder* dec, int enable);
-int decoder_num_steps(const wmdec_decoder* dec);
-int decoder_step_info(const wmdec_decoder* dec, int index, const char** kernel, double* flops, double* bytes);
-int decoder_step_times(const wmdec_decoder* dec, float* ms, int count);
-int decoder_time_step(wmdec_decoder* dec, const void* latent, const void* packed, void* out, int batch,
-                      int step, int reps, float* ms_per_launch, void* stream);
+double decoder_dense_flops_per_frame(const wmdec_decoder* dec);
 
 #ifdef __cplusplus
 }

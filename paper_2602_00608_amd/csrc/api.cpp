@@ -83,6 +83,7 @@ struct Step {
   int from_producer = 0;   // STATS: only merge the moments the producing convolution left behind
   size_t w_off = 0, b_off = 0, gamma_off = 0, beta_off = 0;
   double flops = 0.0, bytes = 0.0;   // algorithmic work / HBM traffic of this step for one frame
+  double flops_dense = 0.0;          // the same with an upsampling convolution priced as nine taps per output
 };
 
 }  // namespace wmdec
@@ -97,7 +98,8 @@ struct wmdec_decoder {
   size_t act_elems_per_frame = 0;   // largest activation tensor, elements per frame
   int attn_t = 0, attn_tpad = 0, attn_c = 0;
   size_t qkv_w_off = 0, qkv_b_off = 0;   // fused [3c][c] projection and its [3c] bias in the packed blob
-  double flops = 0.0;
+  double flops = 0.0;         // executed multiply-adds x 2 of one frame
+  double flops_dense = 0.0;   // 2*k*k*cin*cout per output pixel everywhere (what an unfused graph would execute)
   int launches = 0;
   void* ws = nullptr;
   size_t ws_bytes = 0;
@@ -111,6 +113,17 @@ struct wmdec_decoder {
 };
 
 namespace wmdec {
+
+// the launch-shape part of a CONV step's arguments (pointers left null)
+static ConvArgs step_shape_args(const wmdec_decoder& d, const Step& st, int batch) {
+  ConvArgs a;
+  a.op_dtype = d.cfg.act_dtype; a.res_dtype = a.op_dtype;
+  a.x_dtype = st.src == BUF_LATENT ? d.cfg.latent_dtype : a.op_dtype; a.x_nchw = st.x_nchw;
+  a.y_dtype = st.dst == BUF_OUT ? (int)WMDEC_F32 : a.op_dtype; a.y_nchw = st.y_nchw;
+  a.n = batch; a.h = st.h; a.w = st.w; a.cin = st.cin; a.cout = st.cout; a.ksize = st.ksize; a.upsample = st.upsample;
+  a.stats_groups = d.cfg.groups;
+  return a;
+}
 
 struct Builder {
   wmdec_decoder& d;
@@ -159,12 +172,16 @@ struct Builder {
     Step& s = d.steps.back();
     const double es = (double)dtype_size(d.cfg.act_dtype);
     const double px_out = (double)s.h * s.w, px_in = s.upsample ? px_out / 4 : px_out;
-    s.flops = 2.0 * s.ksize * s.ksize * (double)s.cin * s.cout * px_out;
-    s.bytes = px_in * s.cin * (s.src == BUF_LATENT ? 2.0 : es)                  // input, once
+    s.flops_dense = 2.0 * s.ksize * s.ksize * (double)s.cin * s.cout * px_out;
+    // a phase-decomposed upsampling convolution executes a 2x2 convolution per output: 4/9 of the products.
+    // Only executed work is counted, never the work avoided.
+    s.flops = conv_mfma_uses_phase(step_shape_args(d, s, 1)) ? s.flops_dense * 4.0 / 9.0 : s.flops_dense;
+    s.bytes = px_in * s.cin * (s.src == BUF_LATENT ? (double)dtype_size(d.cfg.latent_dtype) : es)                  // input, once
               + px_out * s.cout * (s.dst == BUF_OUT ? 4.0 : es)                 // output, once
               + (s.res != BUF_NONE ? px_out * s.cout * es : 0.0)                // residual, once
               + (double)s.ksize * s.ksize * s.cin * s.cout * es;                // weights, once
     d.flops += s.flops;
+    d.flops_dense += s.flops_dense;
     d.launches += 1;
   }
   void track(int h, int w, int c) {
@@ -198,17 +215,6 @@ struct Builder {
   }
 };
 
-
-// the launch-shape part of a CONV step's arguments (pointers left null)
-static ConvArgs step_shape_args(const wmdec_decoder& d, const Step& st, int batch) {
-  ConvArgs a;
-  a.op_dtype = d.cfg.act_dtype; a.res_dtype = a.op_dtype;
-  a.x_dtype = st.src == BUF_LATENT ? (int)WMDEC_BF16 : a.op_dtype; a.x_nchw = st.x_nchw;
-  a.y_dtype = st.dst == BUF_OUT ? (int)WMDEC_F32 : a.op_dtype; a.y_nchw = st.y_nchw;
-  a.n = batch; a.h = st.h; a.w = st.w; a.cin = st.cin; a.cout = st.cout; a.ksize = st.ksize; a.upsample = st.upsample;
-  a.stats_groups = d.cfg.groups;
-  return a;
-}
 
 // Statistics passes whose input was written by a convolution that can emit moments in its epilogue become
 // a merge of those moments: the tensor is not read again.  One partial buffer exists, so a producer is used
@@ -266,9 +272,11 @@ static int build_plan(wmdec_decoder& d) {
     d.steps.push_back(tv); d.launches += 1;
     Step f; f.kind = Step::FLASH; f.h = h; f.w = w; f.cin = c0;
     f.flops = 4.0 * (double)(h * w) * (double)(h * w) * c0;
+    f.flops_dense = f.flops;
     f.bytes = 4.0 * h * w * c0 * dtype_size(c.act_dtype);
     d.steps.push_back(f); d.launches += 2;
     d.flops += f.flops;
+    d.flops_dense += f.flops_dense;
     Step p; p.kind = Step::CONV; p.to_attn = 2; p.dst = other(1); p.res = cur; p.h = h; p.w = w; p.cin = c0; p.cout = c0; p.ksize = 1;
     B.conv_params("mid.attn.proj", c0, c0, 1, &p.w_off, &p.b_off);
     d.steps.push_back(p); B.count_conv(p);
@@ -308,7 +316,7 @@ static int build_plan(wmdec_decoder& d) {
   }
   d.weights_bytes = B.off;
   d.packed_bytes = B.poff;
-  fuse_stats_into_producers(d);
+  if (!c.separate_stats_pass) fuse_stats_into_producers(d);
   return WMDEC_OK;
 }
 
@@ -441,6 +449,48 @@ int wmdec_gn_silu_conv3x3(const void* x, int act_dtype, const float* mean, const
                     residual, y, y_dtype, n, h, w, cin, cout, stream);
 }
 
+// shape-only arguments of a 3x3 launch that also emits the moments of its output
+static ConvArgs stats_conv_shape(int act_dtype, int y_dtype, int n, int h, int w, int cin, int cout, int out_groups) {
+  ConvArgs a;
+  a.x_dtype = act_dtype; a.op_dtype = act_dtype; a.res_dtype = act_dtype; a.y_dtype = y_dtype;
+  a.n = n; a.h = h; a.w = w; a.cin = cin; a.cout = cout; a.ksize = 3; a.stats_groups = out_groups;
+  return a;
+}
+
+size_t wmdec_conv_stats_workspace_bytes(int act_dtype, int y_dtype, int n, int h, int w, int cin, int cout, int out_groups) {
+  if (n <= 0 || h <= 0 || w <= 0 || cin <= 0 || cout <= 0 || out_groups <= 0 || !valid_dtype(act_dtype) || !valid_dtype(y_dtype)) return 0;
+  const int slots = conv_mfma_stats_slots(stats_conv_shape(act_dtype, y_dtype, n, h, w, cin, cout, out_groups));
+  return (size_t)n * out_groups * slots * 3 * sizeof(float);
+}
+
+int wmdec_gn_silu_conv3x3_stats(const void* x, int act_dtype, const float* mean, const float* rstd, const float* gamma,
+                                const float* beta, int groups, int apply_silu, const void* w_packed, const float* bias,
+                                const void* residual, void* y, int y_dtype, int n, int h, int w, int cin, int cout,
+                                int out_groups, float out_eps, float* mean_out, float* rstd_out, void* workspace,
+                                size_t workspace_bytes, void* stream) {
+  const char* who = "gn_silu_conv3x3_stats";
+  const int rc = check_conv(who, x, act_dtype, mean, rstd, gamma, beta, groups, w_packed, residual, y, y_dtype, n, h, w, cin, cout);
+  if (rc != WMDEC_OK) return rc;
+  WMDEC_REQUIRE(mean_out && rstd_out, WMDEC_ERR_INVALID_ARG, "%s: null output statistics", who);
+  WMDEC_REQUIRE(out_groups > 0 && cout % out_groups == 0, WMDEC_ERR_SHAPE, "%s: cout %d not divisible by out_groups %d", who, cout, out_groups);
+  WMDEC_REQUIRE(out_eps >= 0.f, WMDEC_ERR_INVALID_ARG, "%s: negative eps", who);
+  ConvArgs a = stats_conv_shape(act_dtype, y_dtype, n, h, w, cin, cout, out_groups);
+  a.x = x; a.mean = mean; a.rstd = mean ? rstd : nullptr; a.gamma = gamma; a.beta = beta;
+  a.groups = mean ? groups : 1; a.silu = (mean && apply_silu) ? 1 : 0;
+  a.wt = w_packed; a.bias = bias; a.res = residual; a.y = y;
+  const int slots = conv_mfma_stats_slots(a);
+  WMDEC_REQUIRE(slots > 0, WMDEC_ERR_UNSUPPORTED,
+                "%s: this shape / type does not take the matrix-core kernel that emits moments (16-bit types, cin %% 32 == 0, "
+                "cout %% 64 == 0, channels per output group a power of two <= 32); use wmdec_gn_stats on y", who);
+  const size_t need = (size_t)n * out_groups * slots * 3 * sizeof(float);
+  WMDEC_REQUIRE(workspace && aligned16(workspace) && workspace_bytes >= need, WMDEC_ERR_WORKSPACE,
+                "%s: workspace needs %zu bytes, got %zu", who, need, workspace_bytes);
+  a.stats_ws = workspace;
+  const int rl = launch_conv(a, (hipStream_t)stream);
+  if (rl != WMDEC_OK) return rl;
+  return launch_gn_finalize(workspace, n * out_groups, slots, out_eps, mean_out, rstd_out, (hipStream_t)stream);
+}
+
 int wmdec_gn_conv1x1(const void* x, int act_dtype, const float* mean, const float* rstd, const float* gamma,
                      const float* beta, int groups, int apply_silu, const void* w_packed, const float* bias,
                      const void* residual, void* y, int y_dtype, int n, int h, int w, int cin, int cout, void* stream) {
@@ -558,6 +608,7 @@ void decoder_default_config(wmdec_decoder_config* cfg) {
   cfg->resblocks_per_level = 3;
   cfg->groups = 32; cfg->eps = 1e-6f; cfg->out_c = 3;
   cfg->act_dtype = WMDEC_F16; cfg->max_batch = 4;
+  cfg->latent_dtype = WMDEC_BF16; cfg->separate_stats_pass = 0;
 }
 
 int decoder_create(const wmdec_decoder_config* cfg, wmdec_decoder** out) {
@@ -577,6 +628,7 @@ int decoder_create(const wmdec_decoder_config* cfg, wmdec_decoder** out) {
   WMDEC_REQUIRE(is_16bit(cfg->act_dtype), WMDEC_ERR_UNSUPPORTED, "decoder_create: act_dtype must be BF16 or F16");
   WMDEC_REQUIRE(cfg->max_batch >= 1 && cfg->max_batch <= 64, WMDEC_ERR_INVALID_ARG, "decoder_create: max_batch must be 1..64");
   WMDEC_REQUIRE(cfg->eps >= 0.f, WMDEC_ERR_INVALID_ARG, "decoder_create: negative eps");
+  WMDEC_REQUIRE(valid_dtype(cfg->latent_dtype), WMDEC_ERR_INVALID_ARG, "decoder_create: bad latent_dtype %d", cfg->latent_dtype);
   wmdec_decoder* d = new (std::nothrow) wmdec_decoder();
   WMDEC_REQUIRE(d, WMDEC_ERR_INVALID_ARG, "decoder_create: out of host memory");
   d->cfg = *cfg;
@@ -596,6 +648,7 @@ size_t decoder_packed_bytes(const wmdec_decoder* dec) { return dec ? dec->packed
 int decoder_num_weights(const wmdec_decoder* dec) { return dec ? (int)dec->params.size() : 0; }
 int decoder_num_launches(const wmdec_decoder* dec) { return dec ? dec->launches : 0; }
 double decoder_flops_per_frame(const wmdec_decoder* dec) { return dec ? dec->flops : 0.0; }
+double decoder_dense_flops_per_frame(const wmdec_decoder* dec) { return dec ? dec->flops_dense : 0.0; }
 
 int decoder_weight_info(const wmdec_decoder* dec, int index, const char** name, size_t* offset, size_t* bytes,
                         int* dtype, int shape[4]) {
@@ -664,7 +717,10 @@ int decoder_set_workspace(wmdec_decoder* dec, void* workspace, size_t bytes) {
 }
 
 // enqueues one step of the plan; *emitted_slots carries the slot count of the last emitting convolution
-static int launch_step(wmdec_decoder* dec, const WsLayout& L, const Step& st, const void* latent, const void* packed,
+// the latent of a run: either `z` holds one latent per frame, or (step != null) frame i is z[0] + (i + 1) * scale * step
+struct LatentSource { const void* z; const void* step; float scale; };
+
+static int launch_step(wmdec_decoder* dec, const WsLayout& L, const Step& st, const LatentSource& latent, const void* packed,
                        void* out, int batch, int* emitted_slots, hipStream_t s) {
   char* ws = (char*)dec->ws;
   const char* pk = (const char*)packed;
@@ -685,7 +741,7 @@ static int launch_step(wmdec_decoder* dec, const WsLayout& L, const Step& st, co
       case Step::CONV: {
         ConvArgs a;
         a.op_dtype = c.act_dtype; a.res_dtype = c.act_dtype;
-        if (st.src == BUF_LATENT) { a.x = latent; a.x_dtype = WMDEC_BF16; a.x_nchw = 1; }
+        if (st.src == BUF_LATENT) { a.x = latent.z; a.x_dtype = c.latent_dtype; a.x_nchw = 1; a.x_step = latent.step; a.step_scale = latent.scale; }
         else if (st.to_attn == 2) { a.x = ws + L.attn_o; a.x_dtype = c.act_dtype; }
         else { a.x = buf(st.src); a.x_dtype = c.act_dtype; }
         if (st.norm) { a.mean = mean; a.rstd = rstd; a.gamma = (const float*)(pk + st.gamma_off); a.beta = (const float*)(pk + st.beta_off); a.groups = c.groups; a.silu = st.silu; }
@@ -724,12 +780,14 @@ static int launch_step(wmdec_decoder* dec, const WsLayout& L, const Step& st, co
   }
 }
 
-int decoder_run(wmdec_decoder* dec, const void* latent, const void* packed, void* out, int batch, void* stream) {
-  WMDEC_REQUIRE(dec && latent && packed && out, WMDEC_ERR_INVALID_ARG, "decoder_run: null pointer");
-  WMDEC_REQUIRE(batch >= 1 && batch <= dec->cfg.max_batch, WMDEC_ERR_INVALID_ARG, "decoder_run: batch %d outside 1..%d", batch, dec->cfg.max_batch);
-  WMDEC_REQUIRE(aligned16(latent) && aligned16(packed) && aligned16(out), WMDEC_ERR_INVALID_ARG, "decoder_run: pointers must be 16-byte aligned");
+static int run_graph(const char* who, wmdec_decoder* dec, const LatentSource& latent, const void* packed, void* out, int batch,
+                     void* stream) {
+  WMDEC_REQUIRE(dec && latent.z && packed && out, WMDEC_ERR_INVALID_ARG, "%s: null pointer", who);
+  WMDEC_REQUIRE(batch >= 1 && batch <= dec->cfg.max_batch, WMDEC_ERR_INVALID_ARG, "%s: batch %d outside 1..%d", who, batch, dec->cfg.max_batch);
+  WMDEC_REQUIRE(aligned16(latent.z) && aligned16(latent.step) && aligned16(packed) && aligned16(out), WMDEC_ERR_INVALID_ARG,
+                "%s: pointers must be 16-byte aligned", who);
   const WsLayout L = ws_layout(dec, batch);
-  WMDEC_REQUIRE(dec->ws && dec->ws_bytes >= L.total, WMDEC_ERR_WORKSPACE, "decoder_run: workspace needs %zu bytes, has %zu", L.total, dec->ws_bytes);
+  WMDEC_REQUIRE(dec->ws && dec->ws_bytes >= L.total, WMDEC_ERR_WORKSPACE, "%s: workspace needs %zu bytes, has %zu", who, L.total, dec->ws_bytes);
   hipStream_t s = (hipStream_t)stream;
   char* ws = (char*)dec->ws;
   if (dec->ws_fresh) {   // once per workspace: the ticket counter of the statistics kernel starts at zero
@@ -748,6 +806,26 @@ int decoder_run(wmdec_decoder* dec, const void* latent, const void* packed, void
     if (prof) WMDEC_HIP(hipEventRecord(dec->events[step_index], s));
   }
   return WMDEC_OK;
+}
+
+int decoder_run(wmdec_decoder* dec, const void* latent, const void* packed, void* out, int batch, void* stream) {
+  return run_graph("decoder_run", dec, LatentSource{latent, nullptr, 0.f}, packed, out, batch, stream);
+}
+
+int decoder_run_extrapolated(wmdec_decoder* dec, const void* z_prev, const void* v_prev, float lambda, const void* packed,
+                             void* out, int batch, void* stream) {
+  WMDEC_REQUIRE(v_prev, WMDEC_ERR_INVALID_ARG, "decoder_run_extrapolated: null motion vector");
+  WMDEC_REQUIRE(isfinite(lambda), WMDEC_ERR_INVALID_ARG, "decoder_run_extrapolated: lambda is not finite");
+  return run_graph("decoder_run_extrapolated", dec, LatentSource{z_prev, v_prev, lambda}, packed, out, batch, stream);
+}
+
+int wmdec_latent_extrapolate(const void* z_prev, const void* v_prev, int dtype, float lambda, int steps, void* z_out,
+                             int out_dtype, size_t count, void* stream) {
+  WMDEC_REQUIRE(z_prev && v_prev && z_out, WMDEC_ERR_INVALID_ARG, "latent_extrapolate: null pointer");
+  WMDEC_REQUIRE(valid_dtype(dtype) && valid_dtype(out_dtype), WMDEC_ERR_INVALID_ARG, "latent_extrapolate: bad dtype");
+  WMDEC_REQUIRE(steps >= 0 && isfinite(lambda), WMDEC_ERR_INVALID_ARG, "latent_extrapolate: bad steps or lambda");
+  if (count == 0) return WMDEC_OK;
+  return launch_axpy(z_prev, v_prev, dtype, (float)steps * lambda, z_out, out_dtype, count, (hipStream_t)stream);
 }
 
 int decoder_time_step(wmdec_decoder* dec, const void* latent, const void* packed, void* out, int batch, int step,
@@ -771,7 +849,7 @@ int decoder_time_step(wmdec_decoder* dec, const void* latent, const void* packed
   hipError_t he = hipEventRecord(e0, s);
   for (int r = 0; r < reps && rc == WMDEC_OK && he == hipSuccess; ++r) {
     int slots = emitted_slots;
-    rc = launch_step(dec, L, dec->steps[step], latent, packed, out, batch, &slots, s);
+    rc = launch_step(dec, L, dec->steps[step], LatentSource{latent, nullptr, 0.f}, packed, out, batch, &slots, s);
   }
   if (he == hipSuccess) he = hipEventRecord(e1, s);
   if (he == hipSuccess) he = hipEventSynchronize(e1);
@@ -812,11 +890,7 @@ int decoder_step_info(const wmdec_decoder* dec, int index, const char** kernel, 
       case Step::QKV_TRANSPOSE_V: *kernel = "transpose_kernel"; break;
       case Step::FLASH: *kernel = "flash_attn_kernel"; break;
       case Step::CONV: {
-        ConvArgs a;   // only the fields the kernel choice looks at
-        a.op_dtype = dec->cfg.act_dtype; a.res_dtype = a.op_dtype;
-        a.x_dtype = st.src == BUF_LATENT ? (int)WMDEC_BF16 : a.op_dtype; a.x_nchw = st.x_nchw;
-        a.y_dtype = st.dst == BUF_OUT ? (int)WMDEC_F32 : a.op_dtype; a.y_nchw = st.y_nchw;
-        a.n = 1; a.h = st.h; a.w = st.w; a.cin = st.cin; a.cout = st.cout; a.ksize = st.ksize; a.upsample = st.upsample;
+        ConvArgs a = step_shape_args(*dec, st, 1);   // only the fields the kernel choice looks at
         a.groups_norm = st.norm; a.silu = st.silu;
         *kernel = conv_kernel_label(a);
         break;

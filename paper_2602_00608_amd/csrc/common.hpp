@@ -69,6 +69,8 @@ struct ConvArgs {
   const void* x = nullptr;       // input activations
   int x_dtype = WMDEC_F32;       // storage type of x
   int x_nchw = 0;                // 1: x is [n,cin,h_in,w_in] (decoder latent), else NHWC
+  const void* x_step = nullptr;  // non-null (few-input-channel kernel only): one tensor shaped like a sample of x, of
+  float step_scale = 0.f;        //   x_dtype; sample i of the input is x[0] + (i + 1) * step_scale * x_step
   const float* mean = nullptr;   // [n*groups] or null: no normalisation
   const float* rstd = nullptr;
   const float* gamma = nullptr;  // [cin]
@@ -102,6 +104,8 @@ int launch_conv_small_cin(const ConvArgs& a, hipStream_t s);
 // is not one it handles (caller falls back to the direct kernel), 0 if launched.
 bool conv_mfma_supported(const ConvArgs& a);
 int launch_conv_mfma(const ConvArgs& a, hipStream_t s);
+// true if the launch evaluates an upsampling convolution per output phase (2x2 taps, 4/9 of the products)
+bool conv_mfma_uses_phase(const ConvArgs& a);
 // moment slots per (sample, group) the MFMA kernel would write for this launch; 0: it cannot emit statistics
 int conv_mfma_stats_slots(const ConvArgs& a);
 const char* conv_mfma_label(const ConvArgs& a);   // instantiation name, valid until the thread's next call
@@ -133,6 +137,8 @@ int launch_pack_upconv(const void* src, int src_dtype, int cout, int cin, void* 
 int launch_transpose(const void* src, int src_dtype, void* dst, int dst_dtype, int batch, int rows, int cols,
                      size_t src_ld, size_t src_batch_stride, size_t dst_ld, size_t dst_batch_stride, hipStream_t s);
 int launch_copy_f32(const float* src, float* dst, size_t count, hipStream_t s);
+// out[i] = fma(scale, v[i], z[i]) in fp32, rounded once to out_dtype; z, v of `dtype`
+int launch_axpy(const void* z, const void* v, int dtype, float scale, void* out, int out_dtype, size_t count, hipStream_t s);
 int launch_zero_u32(void* p, int count, hipStream_t s);   // a fill kernel (safe under graph capture, unlike a memset node)
 
 // kernels_attn.hip

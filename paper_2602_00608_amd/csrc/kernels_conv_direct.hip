@@ -159,10 +159,14 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(DirectParams p) {
 // (tap, output channel) pair as 16 contiguous bytes); a workgroup walks a row segment of 32 pixels whose
 // three-row halo strip sits in LDS (operands rounded to the operand type, zeros outside the image), so every
 // input value is one broadcast LDS read for 256 output channels.  Bias in the epilogue, NHWC output.
+// With x_step the input of sample n is formed while it is staged: x[0] + (n + 1) * step_scale * x_step (one fp32
+// fused multiply-add, then the one rounding to the operand type): n + 1 first-order extrapolation steps of a latent
+// along its motion vector (Alg. 2, hit branch), so a batch of extrapolated latents never exists in memory.
 constexpr int SP = 32;   // pixels per workgroup
 
 template <int CI, typename TW_, typename TO>
 __global__ __launch_bounds__(256) void conv_small_cin_kernel(const void* __restrict__ x, int x_dtype, int x_nchw,
+                                                             const void* __restrict__ x_step, float step_scale,
                                                              const TW_* __restrict__ w, const float* __restrict__ bias,
                                                              TO* __restrict__ y, int h, int w_out, int cin, int cout) {
   __shared__ __align__(16) float s_in[3][SP + 2][CI];
@@ -176,8 +180,11 @@ __global__ __launch_bounds__(256) void conv_small_cin_kernel(const void* __restr
     const int gy = oy + hy - 1, gx = x0 + hx - 1;
     float v = 0.f;
     if (c < cin && gy >= 0 && gy < h && gx >= 0 && gx < w_out) {
-      const size_t idx = x_nchw ? (((size_t)n * cin + c) * h + gy) * w_out + gx : (((size_t)n * h + gy) * w_out + gx) * cin + c;
-      v = round_through<TW_>(load_as_float(x, x_dtype, idx));
+      const size_t xn = x_step ? 0 : n;
+      const size_t idx = x_nchw ? ((xn * cin + c) * h + gy) * w_out + gx : ((xn * h + gy) * w_out + gx) * cin + c;
+      v = load_as_float(x, x_dtype, idx);
+      if (x_step) v = fmaf((float)(n + 1) * step_scale, load_as_float(x_step, x_dtype, idx), v);
+      v = round_through<TW_>(v);
     }
     s_in[hy][hx][c] = v;
   }
@@ -210,9 +217,9 @@ int launch_small_cin_t(const ConvArgs& a, hipStream_t s) {
   const int segs = (a.w + SP - 1) / SP;
   dim3 grid((unsigned)(segs * a.h), (unsigned)((a.cout + 255) / 256), (unsigned)a.n);
   switch (a.y_dtype) {
-    case WMDEC_F32: hipLaunchKernelGGL((conv_small_cin_kernel<CI, TW_, float>), grid, dim3(256), 0, s, a.x, a.x_dtype, a.x_nchw, (const TW_*)a.wt, a.bias, (float*)a.y, a.h, a.w, a.cin, a.cout); break;
-    case WMDEC_BF16: hipLaunchKernelGGL((conv_small_cin_kernel<CI, TW_, bf16_t>), grid, dim3(256), 0, s, a.x, a.x_dtype, a.x_nchw, (const TW_*)a.wt, a.bias, (bf16_t*)a.y, a.h, a.w, a.cin, a.cout); break;
-    default: hipLaunchKernelGGL((conv_small_cin_kernel<CI, TW_, f16_t>), grid, dim3(256), 0, s, a.x, a.x_dtype, a.x_nchw, (const TW_*)a.wt, a.bias, (f16_t*)a.y, a.h, a.w, a.cin, a.cout); break;
+    case WMDEC_F32: hipLaunchKernelGGL((conv_small_cin_kernel<CI, TW_, float>), grid, dim3(256), 0, s, a.x, a.x_dtype, a.x_nchw, a.x_step, a.step_scale, (const TW_*)a.wt, a.bias, (float*)a.y, a.h, a.w, a.cin, a.cout); break;
+    case WMDEC_BF16: hipLaunchKernelGGL((conv_small_cin_kernel<CI, TW_, bf16_t>), grid, dim3(256), 0, s, a.x, a.x_dtype, a.x_nchw, a.x_step, a.step_scale, (const TW_*)a.wt, a.bias, (bf16_t*)a.y, a.h, a.w, a.cin, a.cout); break;
+    default: hipLaunchKernelGGL((conv_small_cin_kernel<CI, TW_, f16_t>), grid, dim3(256), 0, s, a.x, a.x_dtype, a.x_nchw, a.x_step, a.step_scale, (const TW_*)a.wt, a.bias, (f16_t*)a.y, a.h, a.w, a.cin, a.cout); break;
   }
   WMDEC_HIP(hipGetLastError());
   return WMDEC_OK;

@@ -21,8 +21,8 @@
 // staging address (bf16) or, in f16, removed algebraically: the phase mode
 // computes each of the four output phases as a 2x2 convolution on the input grid.
 #include <stdio.h>
-#include <stdlib.h>
 
+#include <mutex>
 #include <type_traits>
 #include <utility>
 
@@ -32,14 +32,6 @@
 
 namespace wmdec {
 namespace {
-
-#ifdef WMDEC_TRACE
-long long* g_trace = nullptr;   // [workgroup][64] timestamps of wavefront 0 (development builds only)
-#define TRACE(i) do { if (p.trace && tid == 0 && (i) < 64) p.trace[(size_t)blockIdx.x * 64 + (i)] = wall_clock64() * 1000 + 0 * clock64(); } while (0)
-#else
-#define TRACE(i) do { } while (0)
-#endif
-int g_tile = -1;   // tile-shape override for sweeps (environment WMDEC_CONV_TILE), -1 = heuristic
 
 struct MfmaParams {
   const void* x; const float* mean; const float* rstd; const float* gamma; const float* beta;
@@ -52,9 +44,6 @@ struct MfmaParams {
   int y_nchw;                    // 1: y is planar [n][cout][h][w] (the frame), else NHWC
   Moments* stats;                // non-null: moments of y per (sample, group, slot); slot = spatial tile * WM + wave row
   int stats_cpg, stats_groups, stats_slots;
-#ifdef WMDEC_TRACE
-  long long* trace;
-#endif
 };
 
 template <typename T> __device__ __forceinline__ void unpack8(const u32x4& v, float* f) {
@@ -154,13 +143,26 @@ __device__ __forceinline__ void epilogue_store(const f32x16 (&acc)[MI][NI], floa
         if (mi + RD < MI)
           rv[mi % RD][j] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(rin) + (unsigned)(max(vec_off(mi + RD, j), 0) * (int)sizeof(T)));
       }
+      // the stored vector; the moments are those of the values as stored (after the rounding to the storage
+      // type), which is what the consumer of the tensor normalises
+      u32x4 packed;
+      if constexpr (sizeof(TO) == 2) {
+        packed = u32x4{pack2<T>(v[0], v[1]), pack2<T>(v[2], v[3]), pack2<T>(v[4], v[5]), pack2<T>(v[6], v[7])};
+      }
       if (stats && off >= 0) {
+        float sv[8];
+        if constexpr (sizeof(TO) == 2) {
+          unpack8<T>(packed, sv);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) sv[e] = v[e];
+        }
         if (st_n == 0.f) {
 #pragma unroll
-          for (int e = 0; e < 8; ++e) st_shift[e] = v[e];
+          for (int e = 0; e < 8; ++e) st_shift[e] = sv[e];
         }
 #pragma unroll
-        for (int e = 0; e < 8; ++e) { const float dv = v[e] - st_shift[e]; st_s[e] += dv; st_q[e] = fmaf(dv, dv, st_q[e]); }
+        for (int e = 0; e < 8; ++e) { const float dv = sv[e] - st_shift[e]; st_s[e] += dv; st_q[e] = fmaf(dv, dv, st_q[e]); }
         st_n += 1.f;
       }
       if (off >= 0) {
@@ -169,8 +171,7 @@ __device__ __forceinline__ void epilogue_store(const f32x16 (&acc)[MI][NI], floa
           reinterpret_cast<f32x4*>(dst)[0] = f32x4{v[0], v[1], v[2], v[3]};
           reinterpret_cast<f32x4*>(dst)[1] = f32x4{v[4], v[5], v[6], v[7]};
         } else {
-          *reinterpret_cast<u32x4*>(dst) =
-              u32x4{pack2<T>(v[0], v[1]), pack2<T>(v[2], v[3]), pack2<T>(v[4], v[5]), pack2<T>(v[6], v[7])};
+          *reinterpret_cast<u32x4*>(dst) = packed;
         }
       }
     }
@@ -462,10 +463,6 @@ void conv_mfma_kernel(MfmaParams p) {
   constexpr int SPREAD = (ACT == 0 || MI * NI > 4) ? -1 : (SPREAD_AVG > 1 ? SPREAD_AVG - 1 : 1);
   f32x4 abv[2];   // table entries of the part being activated and of the next one (sliced activation)
 
-  TRACE(0);
-#ifdef WMDEC_TRACE
-  if (p.trace && tid == 0) p.trace[(size_t)blockIdx.x * 64 + 60] = clock64();
-#endif
   issue(0);
   // (built behind the first chunk's loads, so that its own global loads overlap them)
   // per-channel scale/shift table: a = gamma*rstd, b = beta - mean*a.  With SiLU the table holds -log2(e) * (a, b):
@@ -484,7 +481,6 @@ void conv_mfma_kernel(MfmaParams p) {
   activate_all(0, s_a);
   issue(1);
   __syncthreads();
-  TRACE(1);
   for (int c = 0; c < nchunks; ++c) {
     const bool more = c + 1 < nchunks;
     const int bcur = wcol + c * KK * kk_stride;
@@ -492,7 +488,6 @@ void conv_mfma_kernel(MfmaParams p) {
     const T* buf = s_a + (c & 1) * BUF;
     T* nbuf = s_a + ((c + 1) & 1) * BUF;
     const int c0n = (c + 1) * KC;
-    TRACE(2 + 4 * c);
     if constexpr (SLICED) {
       // Slots FIRST .. SLOTS-1 share the NV*4 words of the next chunk evenly.  All vectors of a thread hold the same
       // channel octet, so the words are taken part by part (word `part` of every vector, then the next part) and
@@ -516,17 +511,13 @@ void conv_mfma_kernel(MfmaParams p) {
       // the last chunk activates a harmless reload into the buffer nobody reads: one instruction stream, no
       // control flow inside the pinned schedule
       mfma_chunk<T, MI, NI, KT, KC, HW_, PS, D, true, SPREAD>(buf, a_off, wrsrc, bcur, bnext, tap_stride, kk_stride, lane16, bq, acc, slice);
-      TRACE(3 + 4 * c);
     } else {
       auto none = [](auto) {};
       mfma_chunk<T, MI, NI, KT, KC, HW_, PS, D, false, -1>(buf, a_off, wrsrc, bcur, bnext, tap_stride, kk_stride, lane16, bq, acc, none);
-      TRACE(3 + 4 * c);
       if (more) activate_all(c0n, nbuf);
     }
     issue(c + 2);
-    TRACE(4 + 4 * c);
     __syncthreads();          // other buffer staged; this one free for chunk c+2
-    TRACE(5 + 4 * c);
   }
 
   // ---- epilogue: bias, residual, one rounding, store (through a wavefront-private LDS patch over the tile buffers)
@@ -543,10 +534,6 @@ void conv_mfma_kernel(MfmaParams p) {
     epilogue_store<T, TO, MI, NI, MTW, MTH, MT_PER_ROW, false>(acc, patch, lane, PH ? 0 : wm * MI, ty0, tx0, co0 + wn * NI * 32, p.bias,
                                                                rin, yout, p.h, p.w_out, p.cout, p.y_nchw != 0, st, p.stats_cpg, p.stats_slots,
                                                                PH ? 2 : 1, PH ? wave >> 1 : 0, PH ? wave & 1 : 0);
-  TRACE(63);
-#ifdef WMDEC_TRACE
-  if (p.trace && tid == 0) p.trace[(size_t)blockIdx.x * 64 + 61] = clock64();
-#endif
 }
 
 template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC, bool PH = false>
@@ -567,9 +554,6 @@ int launch_cfg(const ConvArgs& a, hipStream_t s) {
   p.w_bytes = (int)(packed_elems(PH ? 16 : KS * KS, a.cout, a.cin) * sizeof(T));
   p.stats = (Moments*)a.stats_ws; p.stats_groups = a.stats_groups; p.stats_cpg = a.stats_groups > 0 ? a.cout / a.stats_groups : 1;
   p.stats_slots = p.tiles_x * p.tiles_y * WM;
-#ifdef WMDEC_TRACE
-  p.trace = g_trace;
-#endif
   constexpr int NT = 64 * WM * WN;
   constexpr int NV = (HP * (KC / 8) + NT - 1) / NT;
   size_t smem = (((size_t)2 * tile_pixel_slots(NV * NT / (KC / 8), HP) * (KC + 8) * 2 + 15) & ~(size_t)15) + (size_t)a.cin * sizeof(float2);
@@ -579,12 +563,12 @@ int launch_cfg(const ConvArgs& a, hipStream_t s) {
   void (*kern)(MfmaParams) = !p.norm ? conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 0, PH>
                              : (a.silu ? conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 2, PH>
                                        : conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 1, PH>);
-  static bool attr_set[3] = {false, false, false};   // per instantiation and activation mode
-  const int mode = !p.norm ? 0 : (a.silu ? 2 : 1);
-  if (!attr_set[mode]) {
-    WMDEC_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024));   // two workgroups per compute unit
-    attr_set[mode] = true;
-  }
+  // once per instantiation and activation mode (80 KiB: two workgroups per compute unit)
+  static std::once_flag attr_once[3];
+  hipError_t attr_err = hipSuccess;
+  std::call_once(attr_once[!p.norm ? 0 : (a.silu ? 2 : 1)],
+                 [&] { attr_err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024); });
+  WMDEC_HIP(attr_err);
   hipLaunchKernelGGL(kern, dim3((unsigned)p.total), dim3(NT), smem, s, p);
   WMDEC_HIP(hipGetLastError());
   return WMDEC_OK;
@@ -592,64 +576,61 @@ int launch_cfg(const ConvArgs& a, hipStream_t s) {
 
 // Tile shapes: patch height x width, wavefront rows x columns, 32-channel tiles per wavefront.
 struct TileShape { int th, tw, wm, wn, ni; };
-constexpr TileShape kTiles[] = {
-    {8, 32, 2, 2, 2},    // 0: 256 pixels x 128 channels
-    {4, 32, 2, 2, 2},    // 1: 128 x 128, 4x32 patch
-    {4, 32, 4, 1, 2},    // 2: 128 x 64, 4x32 patch
-    {8, 32, 4, 1, 2},    // 3: 256 x 64
-    {8, 16, 2, 2, 2},    // 4: 128 x 128, 8x16 patch
-    {16, 16, 2, 2, 2},   // 5: 256 x 128, 16x16 patch
-    {8, 16, 4, 1, 2},    // 6: 128 x 64, 8x16 patch
-    {8, 32, 4, 1, 1},    // 7: 256 x 32 (few output channels: the frame)
-    {8, 32, 1, 4, 1},    // 8: 256 x 128 with wavefronts 1x4 (measured: no gain over shape 0; not instantiated)
-    {8, 16, 4, 1, 2},    // 9: phase-decomposed upsampling convolution: 8x16 input pixels (16x32 outputs) x 64 channels
-    {8, 16, 2, 4, 1},    // 10: 128 x 128 with eight wavefronts (measured: no gain on the small layers; not instantiated)
-    {8, 16, 1, 4, 1},    // 11: 128 x 128, every wavefront all pixels x 32 channels: a weight fragment feeds four MFMAs
-                         //     (two in shape 4), which halves the load on the vector L1 (64 B/clk per compute unit)
+enum TileId { T256x128 = 0, T128x128_ROW, T128x64_ROW, T128x128, T128x64, T256x32, T_PHASE, T128x128_1x4, kNumTiles };
+constexpr TileShape kTiles[kNumTiles] = {
+    {8, 32, 2, 2, 2},    // T256x128: 256 pixels x 128 channels
+    {4, 32, 2, 2, 2},    // T128x128_ROW: 128 x 128 on a 4x32 patch (1x1 convolutions)
+    {4, 32, 4, 1, 2},    // T128x64_ROW: 128 x 64 on a 4x32 patch (1x1 convolutions)
+    {8, 16, 2, 2, 2},    // T128x128: 128 x 128 on an 8x16 patch, wavefronts 2x2
+    {8, 16, 4, 1, 2},    // T128x64: 128 x 64 on an 8x16 patch
+    {8, 32, 4, 1, 1},    // T256x32: 256 x 32 (few output channels: the frame)
+    {8, 16, 4, 1, 2},    // T_PHASE: phase-decomposed upsampling convolution: 8x16 input pixels (16x32 outputs) x 64 channels
+    {8, 16, 1, 4, 1},    // T128x128_1x4: 128 x 128, every wavefront all pixels x 32 channels: a weight fragment feeds four
+                         //     MFMAs (two in T128x128), which halves the load on the vector L1 (64 B/clk per compute unit)
 };
 
-// which tile shape a launch uses (3x3: any of the above; 1x1: 0, 1 or 2)
-int pick_tile(const ConvArgs& a) {
-  const long px = (long)a.h * a.w;   // per sample: the tiling, hence every summation order, does not depend on the batch
+// which tile shape a launch uses; a function of the per-sample shape only, so that the tiling, hence every summation
+// order, does not depend on the batch
+TileId pick_tile(const ConvArgs& a) {
+  const long px = (long)a.h * a.w;
   const bool n128 = a.cout % 128 == 0;
   if (a.ksize == 3) {
-    // phase decomposition (needs a.wt_phase at launch) for f16 only: pre-added weights rounded to bf16 would cost
-    // that type a visible part of its error budget
-    if (a.upsample && a.op_dtype == WMDEC_F16 && a.cout % 64 == 0 && g_tile != 0) return 9;
-    if (a.cout <= 32) return 7;
+    if (conv_mfma_uses_phase(a)) return T_PHASE;
+    if (a.cout <= 32) return T256x32;
+    if (!n128) return T128x64;
     // 256-pixel tiles when that still gives three per compute unit; else 128-pixel tiles, with one weight
-    // fragment per four MFMAs (shape 11) unless the layer leaves compute units empty anyway (shape 4)
+    // fragment per four MFMAs unless the layer leaves compute units empty anyway
     const long work = px * (a.cout / 128);
-    int t = (g_tile == 0 || g_tile == 4 || g_tile == 6 || g_tile == 11) ? g_tile
-            : (n128 && work >= 256L * 256 * 3) ? 0 : (n128 ? (work >= 128L * 256 * 2 ? 11 : 4) : 6);
-    if (!n128) t = 6;
-    return t;
+    return work >= 256L * 256 * 3 ? T256x128 : (work >= 128L * 256 * 2 ? T128x128_1x4 : T128x128);
   }
-  if (n128 && a.cin % 64 == 0 && px * (a.cout / 128) >= 256L * 256 * 2) return 0;
-  return n128 ? 1 : 2;
+  if (n128 && a.cin % 64 == 0 && px * (a.cout / 128) >= 256L * 256 * 2) return T256x128;
+  return n128 ? T128x128_ROW : T128x64_ROW;
 }
 
 template <typename T, typename TO>
 int launch_3x3(const ConvArgs& a, hipStream_t s) {
   switch (pick_tile(a)) {
-    case 0: return launch_cfg<T, TO, 8, 32, 2, 2, 2, 3, 32>(a, s);
-    case 4: return launch_cfg<T, TO, 8, 16, 2, 2, 2, 3, 32>(a, s);
-    case 6: return launch_cfg<T, TO, 8, 16, 4, 1, 2, 3, 32>(a, s);
-    case 9: return launch_cfg<T, TO, 8, 16, 4, 1, 2, 3, 32, true>(a, s);
-    case 11: return launch_cfg<T, TO, 8, 16, 1, 4, 1, 3, 32>(a, s);
+    case T256x128: return launch_cfg<T, TO, 8, 32, 2, 2, 2, 3, 32>(a, s);
+    case T128x128: return launch_cfg<T, TO, 8, 16, 2, 2, 2, 3, 32>(a, s);
+    case T128x64: return launch_cfg<T, TO, 8, 16, 4, 1, 2, 3, 32>(a, s);
+    case T_PHASE: return launch_cfg<T, TO, 8, 16, 4, 1, 2, 3, 32, true>(a, s);
+    case T128x128_1x4: return launch_cfg<T, TO, 8, 16, 1, 4, 1, 3, 32>(a, s);
     default: return launch_cfg<T, TO, 8, 32, 4, 1, 1, 3, 32>(a, s);
   }
 }
 
+// chunk of input channels a 1x1 launch stages at a time: 64 halves the barriers
+int chunk_1x1(const ConvArgs& a) { return a.cin % 64 == 0 ? 64 : 32; }
+
 template <typename T, typename TO>
 int launch_1x1(const ConvArgs& a, hipStream_t s) {
-  const int t = pick_tile(a);
-  if (a.cin % 64 == 0) {   // 64-channel chunks: half the barriers
-    if (t == 0) return launch_cfg<T, TO, 8, 32, 2, 2, 2, 1, 64>(a, s);
-    if (t == 1) return launch_cfg<T, TO, 4, 32, 2, 2, 2, 1, 64>(a, s);
+  const TileId t = pick_tile(a);
+  if (chunk_1x1(a) == 64) {
+    if (t == T256x128) return launch_cfg<T, TO, 8, 32, 2, 2, 2, 1, 64>(a, s);
+    if (t == T128x128_ROW) return launch_cfg<T, TO, 4, 32, 2, 2, 2, 1, 64>(a, s);
     return launch_cfg<T, TO, 4, 32, 4, 1, 2, 1, 64>(a, s);
   }
-  if (t == 1) return launch_cfg<T, TO, 4, 32, 2, 2, 2, 1, 32>(a, s);
+  if (t == T128x128_ROW) return launch_cfg<T, TO, 4, 32, 2, 2, 2, 1, 32>(a, s);
   return launch_cfg<T, TO, 4, 32, 4, 1, 2, 1, 32>(a, s);
 }
 
@@ -660,10 +641,6 @@ int launch_type(const ConvArgs& a, hipStream_t s) {
 }
 
 }  // namespace
-
-#ifdef WMDEC_TRACE
-extern "C" void wmdec_debug_set_trace(void* buf) { g_trace = (long long*)buf; }
-#endif
 
 bool conv_mfma_supported(const ConvArgs& a) {
   if (!is_16bit(a.op_dtype) || a.x_dtype != a.op_dtype) return false;
@@ -679,45 +656,36 @@ bool conv_mfma_supported(const ConvArgs& a) {
   return true;
 }
 
-static void read_env_once() {
-  static bool init = false;
-  if (!init) { const char* t = getenv("WMDEC_CONV_TILE"); g_tile = t ? atoi(t) : -1; init = true; }
+// Phase decomposition of an upsampling convolution (needs a.wt_phase at launch), f16 only: pre-added weights rounded
+// to bf16 would cost that type a visible part of its error budget.
+bool conv_mfma_uses_phase(const ConvArgs& a) {
+  return conv_mfma_supported(a) && a.ksize == 3 && a.upsample && a.op_dtype == WMDEC_F16 && a.cout % 64 == 0;
 }
 
 int conv_mfma_stats_slots(const ConvArgs& a) {
-  read_env_once();
   if (!conv_mfma_supported(a) || a.y_nchw || a.stats_groups <= 0 || a.cout % a.stats_groups != 0) return 0;
   const int cpg = a.cout / a.stats_groups;
   if ((cpg & (cpg - 1)) != 0 || cpg > 32) return 0;   // a group must sit inside one wavefront's 64-channel run
-  int t = pick_tile(a);
-  if (a.ksize == 1 && a.cin % 64 != 0 && t == 0) t = 1;
+  const TileId t = pick_tile(a);
   const TileShape& ts = kTiles[t];
-  const int w_t = t == 9 ? a.w / 2 : a.w, h_t = t == 9 ? a.h / 2 : a.h;
+  const int w_t = t == T_PHASE ? a.w / 2 : a.w, h_t = t == T_PHASE ? a.h / 2 : a.h;
   return ((w_t + ts.tw - 1) / ts.tw) * ((h_t + ts.th - 1) / ts.th) * ts.wm;
 }
 
 // the instantiation a launch would use, spelled like a profiler prints it
 const char* conv_mfma_label(const ConvArgs& a) {
   static thread_local char buf[160];
-  read_env_once();
-  int t = pick_tile(a), kc = 32;
-  if (a.ksize == 1) {
-    if (a.cin % 64 == 0) kc = 64;
-    else if (t == 0) t = 1;
-    if (t != 0 && t != 1) t = 2;
-  } else if (t != 0 && t != 4 && t != 6 && t != 9 && t != 11) {
-    t = 7;
-  }
+  const TileId t = pick_tile(a);
+  const int kc = a.ksize == 1 ? chunk_1x1(a) : 32;
   const TileShape& ts = kTiles[t];
   const char* ty = a.op_dtype == WMDEC_BF16 ? "wmdec::bf16_t" : "wmdec::f16_t";
   const int act = a.mean == nullptr && !a.groups_norm ? 0 : (a.silu ? 2 : 1);
   snprintf(buf, sizeof(buf), "conv_mfma_kernel<%s, %s, %d, %d, %d, %d, %d, %d, %d, %d, %s>", ty,
-           a.y_dtype == WMDEC_F32 ? "float" : ty, ts.th, ts.tw, ts.wm, ts.wn, ts.ni, a.ksize, kc, act, t == 9 ? "true" : "false");
+           a.y_dtype == WMDEC_F32 ? "float" : ty, ts.th, ts.tw, ts.wm, ts.wn, ts.ni, a.ksize, kc, act, t == T_PHASE ? "true" : "false");
   return buf;
 }
 
 int launch_conv_mfma(const ConvArgs& a, hipStream_t s) {
-  read_env_once();
   return a.op_dtype == WMDEC_BF16 ? launch_type<bf16_t>(a, s) : launch_type<f16_t>(a, s);
 }
 

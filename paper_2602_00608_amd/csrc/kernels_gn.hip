@@ -10,7 +10,19 @@
 // kernel gn_stats_vec, whose last workgroup per sample does the merge; everything
 // else takes gn_partial_any followed by gn_finalize, which also merges the
 // moments a convolution emitted from its epilogue.
+//
+// Hardware assumption of the single-launch kernel (gfx950 only, checked below): its cross-workgroup hand-over uses
+// no release / acquire fence, because an agent-scope fence on this chip writes back or invalidates the whole L2
+// of the XCD (microseconds per wavefront).  Instead every shared word is itself accessed with agent-scope atomic
+// stores and loads, which gfx950 executes as write-through stores / L2-bypassing loads of memory that is coherent
+// across the XCDs; the publishing wavefront waits until the memory system has acknowledged its stores (vmcnt = 0)
+// before it takes the ticket, and only the workgroup that draws the last ticket reads.  Under the language memory
+// model the relaxed accesses alone would not order the stores before the ticket; the wait does, on this hardware.
 #include "moments.hpp"
+
+#if defined(__HIP_DEVICE_COMPILE__) && !defined(__gfx950__)
+#error "kernels_gn.hip relies on gfx950 memory behaviour (see the note on the single-launch kernel)"
+#endif
 
 namespace wmdec {
 namespace {
@@ -44,12 +56,15 @@ __device__ __forceinline__ Moments load_device(const Moments* p) {
 }
 __device__ __forceinline__ void wait_stores() {
   __builtin_amdgcn_sched_barrier(0);
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): every store of this wavefront has been acknowledged
+  // s_waitcnt immediate of gfx9-family chips: vmcnt in bits 3:0 and 15:14, expcnt in 6:4, lgkmcnt in 11:8
+  constexpr int kVmcnt0 = 0, kExpcntAny = 7 << 4, kLgkmcntAny = 0xF << 8;
+  __builtin_amdgcn_s_waitcnt(kVmcnt0 | kExpcntAny | kLgkmcntAny);   // every store of this wavefront has been acknowledged
   __builtin_amdgcn_sched_barrier(0);
 }
 
 constexpr int kVecThreads = 1024;
 constexpr int kVecMaxChunks = 256;
+constexpr int kVecMaxGroups = 256;
 
 template <typename T, int V, bool MASKED>
 __device__ __forceinline__ void gn_accumulate(const Vec16<T>* base, int p, int p1, int ppi, int vp, const float* shift,
@@ -80,7 +95,7 @@ __global__ __launch_bounds__(kVecThreads) void gn_stats_vec(const T* __restrict_
   constexpr int V = Vec16<T>::N;
   constexpr int U = 8;
   __shared__ float2 s_e[kVecThreads * V];   // (sum, sum of squares) per (pixel lane, channel)
-  __shared__ Moments s_g[kVecThreads];      // the slab's moments per group
+  __shared__ Moments s_g[kVecMaxGroups];    // the slab's moments per group
   __shared__ unsigned s_last;
   const int tid = threadIdx.x;
   const int vp = c / V;           // vectors per pixel
@@ -237,7 +252,7 @@ Plan make_plan(int x_dtype, int n, int h, int w, int c, int groups) {
   const int cpg = c / groups;
   Plan p;
   const bool divisible = (c % V == 0) && (kVecThreads % (c / V) == 0) && c <= kVecThreads;
-  p.vec = divisible && (cpg & (cpg - 1)) == 0 && cpg <= 64;   // groups are runs of 2^k lanes in the channel reduction
+  p.vec = divisible && (cpg & (cpg - 1)) == 0 && cpg <= 64 && groups <= kVecMaxGroups;   // groups are runs of 2^k lanes in the channel reduction
   p.chunks = pick_chunks(pixels, c, V, p.vec);
   p.chunk_pixels = (pixels + p.chunks - 1) / p.chunks;
   if (p.vec) {

@@ -110,6 +110,26 @@ __global__ __launch_bounds__(256) void copy_f32_kernel(const float* __restrict__
   if (i < count) dst[i] = src[i];
 }
 
+// one first-order extrapolation step count folded into `scale`: out = z + scale * v (Alg. 2, hit branch)
+template <typename S, typename D>
+__global__ __launch_bounds__(256) void axpy_kernel(const S* __restrict__ z, const S* __restrict__ v, float scale,
+                                                   D* __restrict__ out, size_t count) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < count) out[i] = from_float<D>(fmaf(scale, to_float(v[i]), to_float(z[i])));
+}
+
+template <typename S>
+int axpy_s(const void* z, const void* v, float scale, void* out, int out_dtype, size_t count, hipStream_t s) {
+  const dim3 grid((unsigned)((count + 255) / 256));
+  switch (out_dtype) {
+    case WMDEC_F32: hipLaunchKernelGGL((axpy_kernel<S, float>), grid, dim3(256), 0, s, (const S*)z, (const S*)v, scale, (float*)out, count); break;
+    case WMDEC_BF16: hipLaunchKernelGGL((axpy_kernel<S, bf16_t>), grid, dim3(256), 0, s, (const S*)z, (const S*)v, scale, (bf16_t*)out, count); break;
+    default: hipLaunchKernelGGL((axpy_kernel<S, f16_t>), grid, dim3(256), 0, s, (const S*)z, (const S*)v, scale, (f16_t*)out, count); break;
+  }
+  WMDEC_HIP(hipGetLastError());
+  return WMDEC_OK;
+}
+
 template <typename S, typename D>
 int pack_t(const void* src, void* dst, int cout, int cin, int k, int row_off, int rows_total, hipStream_t s) {
   const size_t total = packed_elems(k * k, rows_total, cin);
@@ -211,6 +231,14 @@ int launch_transpose(const void* src, int src_dtype, void* dst, int dst_dtype, i
     case WMDEC_F32: return transpose_s<float>(src, dst, dst_dtype, batch, rows, cols, src_ld, src_batch_stride, dst_ld, dst_batch_stride, s);
     case WMDEC_BF16: return transpose_s<bf16_t>(src, dst, dst_dtype, batch, rows, cols, src_ld, src_batch_stride, dst_ld, dst_batch_stride, s);
     default: return transpose_s<f16_t>(src, dst, dst_dtype, batch, rows, cols, src_ld, src_batch_stride, dst_ld, dst_batch_stride, s);
+  }
+}
+
+int launch_axpy(const void* z, const void* v, int dtype, float scale, void* out, int out_dtype, size_t count, hipStream_t s) {
+  switch (dtype) {
+    case WMDEC_F32: return axpy_s<float>(z, v, scale, out, out_dtype, count, s);
+    case WMDEC_BF16: return axpy_s<bf16_t>(z, v, scale, out, out_dtype, count, s);
+    default: return axpy_s<f16_t>(z, v, scale, out, out_dtype, count, s);
   }
 }
 

@@ -28,12 +28,13 @@ class DecoderConfig(ctypes.Structure):
     _fields_ = [("latent_c", ctypes.c_int), ("latent_h", ctypes.c_int), ("latent_w", ctypes.c_int),
                 ("num_levels", ctypes.c_int), ("level_channels", ctypes.c_int * 4),
                 ("resblocks_per_level", ctypes.c_int), ("groups", ctypes.c_int), ("eps", ctypes.c_float),
-                ("out_c", ctypes.c_int), ("act_dtype", ctypes.c_int), ("max_batch", ctypes.c_int)]
+                ("out_c", ctypes.c_int), ("act_dtype", ctypes.c_int), ("max_batch", ctypes.c_int),
+                ("latent_dtype", ctypes.c_int), ("separate_stats_pass", ctypes.c_int)]
 
 
 _vp, _i, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
 
-# name -> (restype, argtypes): every symbol include/wmdec.h declares
+# name -> (restype, argtypes): every symbol include/wmdec.h and include/wmdec_measure.h declare
 SIGNATURES = {
     "wmdec_last_error": (ctypes.c_char_p, []),
     "wmdec_status_string": (ctypes.c_char_p, [_i]),
@@ -42,6 +43,9 @@ SIGNATURES = {
     "wmdec_conv_packed_bytes": (_sz, [_i] * 4),
     "wmdec_pack_conv_weights": (_i, [_vp, _i, _i, _i, _i, _vp, _i, _vp]),
     "wmdec_gn_silu_conv3x3": (_i, [_vp, _i, _vp, _vp, _vp, _vp, _i, _i, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp]),
+    "wmdec_conv_stats_workspace_bytes": (_sz, [_i] * 8),
+    "wmdec_gn_silu_conv3x3_stats": (_i, [_vp, _i, _vp, _vp, _vp, _vp, _i, _i, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i,
+                                         _i, _f, _vp, _vp, _vp, _sz, _vp]),
     "wmdec_gn_conv1x1": (_i, [_vp, _i, _vp, _vp, _vp, _vp, _i, _i, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp]),
     "wmdec_upconv_packed_bytes": (_sz, [_i] * 3),
     "wmdec_pack_upconv_weights": (_i, [_vp, _i, _i, _i, _vp, _i, _vp]),
@@ -64,8 +68,11 @@ SIGNATURES = {
     "decoder_workspace_bytes": (_sz, [_vp, _i]),
     "decoder_set_workspace": (_i, [_vp, _vp, _sz]),
     "decoder_run": (_i, [_vp, _vp, _vp, _vp, _i, _vp]),
+    "decoder_run_extrapolated": (_i, [_vp, _vp, _vp, _f, _vp, _vp, _i, _vp]),
+    "wmdec_latent_extrapolate": (_i, [_vp, _vp, _i, _f, _i, _vp, _i, _sz, _vp]),
     "decoder_num_launches": (_i, [_vp]),
     "decoder_flops_per_frame": (ctypes.c_double, [_vp]),
+    "decoder_dense_flops_per_frame": (ctypes.c_double, [_vp]),
     "decoder_set_profiling": (_i, [_vp, _i]),
     "decoder_num_steps": (_i, [_vp]),
     "decoder_step_info": (_i, [_vp, _i, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_double),
@@ -150,6 +157,21 @@ def gn_silu_conv3x3(x, mean, rstd, gamma, beta, groups, apply_silu, w_packed, bi
           x.shape[3], y.shape[3])
 
 
+def conv_stats_workspace_bytes(act_dtype, y_dtype, n, h, w, cin, cout, out_groups):
+    return lib().wmdec_conv_stats_workspace_bytes(act_dtype, y_dtype, n, h, w, cin, cout, out_groups)
+
+
+def gn_silu_conv3x3_stats(x, mean, rstd, gamma, beta, groups, apply_silu, w_packed, bias, residual, y,
+                          out_groups, out_eps, mean_out, rstd_out, workspace):
+    """gn_silu_conv3x3 that also returns mean / rstd of its own output y per (sample, output group)."""
+    n, h, w, _ = y.shape
+    _check(lib().wmdec_gn_silu_conv3x3_stats(
+        _ptr(x), dtype_enum(x), _ptr(mean), _ptr(rstd), _ptr(gamma), _ptr(beta), groups, int(apply_silu),
+        _ptr(w_packed), _ptr(bias), _ptr(residual), _ptr(y), dtype_enum(y), n, h, w, x.shape[3], y.shape[3],
+        out_groups, out_eps, _ptr(mean_out), _ptr(rstd_out), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream()))
+
+
 def gn_conv1x1(x, mean, rstd, gamma, beta, groups, apply_silu, w_packed, bias, residual, y):
     _conv(lib().wmdec_gn_conv1x1, x, mean, rstd, gamma, beta, groups, apply_silu, w_packed, bias, residual, y,
           x.shape[3], y.shape[3])
@@ -197,6 +219,12 @@ def attention(x, mean, rstd, gamma, beta, groups, wqkv_packed, bqkv, wo_packed, 
                                  _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
 
 
+def latent_extrapolate(z_prev, v_prev, lam, steps, z_out):
+    """z_out = z_prev + steps * lam * v_prev (fp32 fused multiply-add, one rounding to z_out's type)."""
+    _check(lib().wmdec_latent_extrapolate(_ptr(z_prev), _ptr(v_prev), dtype_enum(z_prev), lam, steps, _ptr(z_out),
+                                          dtype_enum(z_out), z_prev.numel(), _stream()))
+
+
 # ------------------------------------------------------------------ decoder
 def decoder_default_config():
     cfg = DecoderConfig()
@@ -239,6 +267,9 @@ class Decoder:
 
     def flops_per_frame(self):
         return lib().decoder_flops_per_frame(self.handle)
+
+    def dense_flops_per_frame(self):
+        return lib().decoder_dense_flops_per_frame(self.handle)
 
     def weight_table(self):
         """[(name, offset, bytes, dtype_enum, shape)] of the canonical blob."""
@@ -288,6 +319,11 @@ class Decoder:
         _check(lib().decoder_time_step(self.handle, _ptr(latent), _ptr(packed), _ptr(out), latent.shape[0], step, reps,
                                        ctypes.byref(ms), _stream()))
         return ms.value
+
+    def run_extrapolated(self, z_prev, v_prev, lam, packed, out):
+        """Frame j of out = decode(z_prev + (j + 1) * lam * v_prev), j = 0..out.shape[0]-1."""
+        _check(lib().decoder_run_extrapolated(self.handle, _ptr(z_prev), _ptr(v_prev), lam, _ptr(packed), _ptr(out),
+                                              out.shape[0], _stream()))
 
     def run(self, latent, packed, out):
         _check(lib().decoder_run(self.handle, _ptr(latent), _ptr(packed), _ptr(out), latent.shape[0], _stream()))

@@ -13,7 +13,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def header_symbols():
-    text = open(os.path.join(ROOT, "include", "wmdec.h")).read()
+    inc = os.path.join(ROOT, "include")
+    text = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return set(re.findall(r"\b((?:wmdec|decoder)_[a-z0-9_]+)\s*\(", text))
 
@@ -52,28 +53,38 @@ def test_default_config_and_weight_table_match_input_recipe():
     assert offs == sorted(offs) and dec.weights_bytes() >= offs[-1] + table[-1][2]
     nparam = sum(int(np.prod(s[1])) for s in spec)
     assert 49_000_000 < nparam < 50_000_000          # ~49.5 M parameters
-    # algorithmic work of one frame: 3329 GFLOP (convs) incl. 59.7 GFLOP attention core
-    assert abs(dec.flops_per_frame() / 1e9 - 3329) < 5
+    # work of one frame: 3329 GFLOP with every convolution priced at nine taps (incl. 59.7 GFLOP attention core);
+    # the default (f16) decoder evaluates its three upsampling convolutions per output phase and executes 2820
+    assert abs(dec.dense_flops_per_frame() / 1e9 - 3329) < 5
+    assert abs(dec.flops_per_frame() / 1e9 - 2820) < 5
     assert dec.workspace_bytes(1) > 3 * 480 * 720 * 256 * 2
     assert dec.workspace_bytes(5) == 0                # beyond max_batch
     dec.close()
 
 
 def test_flops_independent_count():
-    """Recount the decoder's FLOPs from the weight spec: every conv weight contributes
-    2*k*k*cin*cout per output pixel at the resolution its name implies."""
+    """Recount the decoder's FLOPs from the weight spec: every conv weight contributes 2*k*k*cin*cout per output
+    pixel at the resolution its name implies.  Only executed work counts: where an upsampling convolution is
+    evaluated per output phase (the f16 decoder) it executes 2x2 taps per output, 4/9 of the nine-tap figure; the
+    bf16 decoder keeps the nine-tap form."""
     res = {"conv_in": 1, "mid": 1, "up.0": 1, "up.1": 2, "up.2": 4, "up.3": 8, "conv_out": 8}
-    total = 0.0
+    dense = phase = 0.0
     for name, shape in synth.decoder_weight_spec():
         if not name.endswith(".w"):
             continue
         key = name[:-2].split(".res")[0].split(".attn")[0].split(".upsample")[0]
         s = res[key] * (2 if ".upsample" in name else 1)
-        total += 2.0 * np.prod(shape) * (60 * s) * (90 * s)
-    total += 4.0 * 5400 * 5400 * 512
-    dec = wmdec.Decoder()
-    assert abs(dec.flops_per_frame() - total) / total < 1e-12
-    dec.close()
+        f = 2.0 * np.prod(shape) * (60 * s) * (90 * s)
+        dense += f
+        phase += f * 4.0 / 9.0 if ".upsample" in name else f
+    attn = 4.0 * 5400 * 5400 * 512
+    for act, executed in ((wmdec.F16, phase + attn), (wmdec.BF16, dense + attn)):
+        cfg = wmdec.decoder_default_config()
+        cfg.act_dtype = act
+        dec = wmdec.Decoder(cfg)
+        assert abs(dec.flops_per_frame() - executed) / executed < 1e-12
+        assert abs(dec.dense_flops_per_frame() - (dense + attn)) / (dense + attn) < 1e-12
+        dec.close()
 
 
 def test_step_accounting_adds_up():

@@ -82,6 +82,85 @@ def test_workload2_upsample_stage_reduced(dtype):
     assert err <= G.TOL[dtype], err
 
 
+def staged_resblock(xd, x, p, dtype):
+    """A C -> C ResBlock through the per-op entry points at a size where every stage is compared with the oracle at
+    its own output: statistics, the first convolution as stored in `dtype`, statistics of that stored tensor, and
+    the block output in fp32.  Every stage's oracle input is what the GPU stage consumed (the stored tensor), so an
+    error is charged to the stage that made it.  Returns the errors by stage."""
+    groups, eps = 32, 1e-6
+    n, h, w, c = xd.shape
+    t = G.TORCH[dtype]
+    errs = {}
+    m1, r1 = G.gn_stats(xd, groups, eps)
+    wm, wr = ref.gn_stats(x, groups, eps)
+    errs["stats1"] = max(float(np.max(np.abs(m1.cpu().numpy() - wm.ravel()) * wr.ravel())),
+                         float(np.max(np.abs(r1.cpu().numpy() / wr.ravel() - 1.0))))
+    hbuf = torch.empty((n, h, w, c), dtype=t, device="cuda")
+    wmdec.gn_silu_conv3x3(xd, m1, r1, G.dev_f32(p["norm1.gamma"]), G.dev_f32(p["norm1.beta"]), groups, True,
+                          G.pack(p["conv1.w"], dtype), G.dev_f32(p["conv1.b"]), None, hbuf)
+    want_h = ref.conv2d(ref.group_norm(x, groups, eps, p["norm1.gamma"], p["norm1.beta"], True), p["conv1.w"], p["conv1.b"])
+    got_h = G.host_nchw(hbuf)
+    errs["conv1"] = ref.rel_err(got_h, want_h)
+    m2, r2 = G.gn_stats(hbuf, groups, eps)
+    wm2, wr2 = ref.gn_stats(got_h, groups, eps)
+    errs["stats2"] = max(float(np.max(np.abs(m2.cpu().numpy() - wm2.ravel()) * wr2.ravel())),
+                         float(np.max(np.abs(r2.cpu().numpy() / wr2.ravel() - 1.0))))
+    y = torch.empty((n, h, w, c), dtype=torch.float32, device="cuda")
+    wmdec.gn_silu_conv3x3(hbuf, m2, r2, G.dev_f32(p["norm2.gamma"]), G.dev_f32(p["norm2.beta"]), groups, True,
+                          G.pack(p["conv2.w"], dtype), G.dev_f32(p["conv2.b"]), xd, y)
+    torch.cuda.synchronize()
+    want_y = ref.conv2d(ref.group_norm(got_h, groups, eps, p["norm2.gamma"], p["norm2.beta"], True), p["conv2.w"], p["conv2.b"]) + x
+    got_y = G.host_nchw(y)
+    errs["conv2"] = ref.rel_err(got_y, want_y)
+    errs["block"] = ref.rel_err(got_y, ref.resblock(x, p, groups, eps))
+    return errs
+
+
+def check_staged(errs, dtype):
+    print(dtype, {k: float("%.3g" % v) for k, v in errs.items()})
+    assert errs["stats1"] < 2e-5 and errs["stats2"] < 2e-5, errs
+    assert errs["conv1"] <= G.TOL[dtype], errs          # stored in the 16-bit type
+    assert errs["conv2"] <= G.TOL[dtype] / 2, errs      # fp32 output of 16-bit operands
+    assert errs["block"] <= G.TOL[dtype], errs
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_workload3_resblock_full_size(dtype):
+    """Workload 3 as stated: x[1,128,480,720], GN(32) -> SiLU -> conv 128->128, twice, + x.  At this size the
+    convolutions take the 256-pixel x 128-channel tile (1380 workgroups), compared here at their own outputs."""
+    x = synth.activation(2, (1, 128, 480, 720), True)
+    p = resblock_params(synth.weight_seed(2), 128, 128, True)
+    check_staged(staged_resblock(G.dev_nhwc(x, dtype), x, p, dtype), dtype)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_workload2_upsample_stage_full_size(dtype):
+    """Workload 2 as stated: x[1,256,120,180] -> nearest-2x -> conv3x3 256->256 -> ResBlock(256) at 240x360.  The
+    upsampling convolution (phase-decomposed in f16: 2760 workgroups; nine taps with the gather in bf16) and the
+    ResBlock convolutions (128-pixel tile with one weight fragment per four MFMAs) are each compared at their own
+    output."""
+    x = synth.activation(1, (1, 256, 120, 180), True)
+    r = np.random.default_rng(synth.weight_seed(1))
+    wu, bu = synth.conv_params(r, 256, 256, 3, True)
+    p = resblock_params(synth.weight_seed(1) + 1, 256, 256, True)
+    xd = G.dev_nhwc(x, dtype)
+    u = torch.empty((1, 240, 360, 256), dtype=G.TORCH[dtype], device="cuda")
+    wmdec.upsample2x_conv3x3(xd, G.pack_upconv(wu, dtype), G.dev_f32(bu), u)
+    torch.cuda.synchronize()
+    got_u = G.host_nchw(u)
+    want_u = ref.upconv(x, wu, bu)
+    eu = ref.rel_err(got_u, want_u)
+    print(dtype, "upconv", float("%.3g" % eu))
+    assert eu <= G.TOL[dtype], eu
+    errs = staged_resblock(u, got_u.astype(np.float32), p, dtype)
+    check_staged(errs, dtype)
+    # the whole stage against the oracle's own chain (errors of the three convolutions accumulate)
+    y = resblock_gpu(u, p, dtype, 32, 1e-6, "f32")
+    e = ref.rel_err(G.host_nchw(y), ref.resblock(want_u, p, 32, 1e-6))
+    print(dtype, "stage", float("%.3g" % e))
+    assert e <= G.TOL[dtype], e
+
+
 # ------------------------------------------------------------------ decoder_run
 def make_blob(dec, weights):
     """Canonical weight blob (bytes) from name -> float32 array, laid out by the library's own table."""
@@ -94,17 +173,28 @@ def make_blob(dec, weights):
     return torch.from_numpy(blob).cuda()
 
 
-def run_decoder(cfg, weights, z, batch=None):
+def dev_latent(z, cfg):
+    """numpy float32 latent (bf16-representable unless the decoder takes fp32 latents) -> device tensor of cfg.latent_dtype."""
+    if cfg.latent_dtype == wmdec.BF16:
+        return torch.from_numpy(synth.bf16_bits(z).view(np.int16)).view(torch.bfloat16).cuda()
+    return torch.from_numpy(np.ascontiguousarray(z, np.float32)).to(wmdec.ENUM2TORCH[cfg.latent_dtype]).cuda()
+
+
+def run_decoder(cfg, weights, z, extrapolate=None):
+    """decoder_run on z[n,...]; with extrapolate = (v, lam, frames): decoder_run_extrapolated from the single latent z."""
     dec = wmdec.Decoder(cfg)
     packed = torch.empty(dec.packed_bytes(), dtype=torch.uint8, device="cuda")
     dec.pack_weights(make_blob(dec, weights), packed)
-    n = z.shape[0]
+    n = z.shape[0] if extrapolate is None else extrapolate[2]
     ws = torch.empty(dec.workspace_bytes(n), dtype=torch.uint8, device="cuda")
     dec.set_workspace(ws)
-    zd = torch.from_numpy(synth.bf16_bits(z).view(np.int16)).view(torch.bfloat16).cuda()
+    zd = dev_latent(z, cfg)
     scale = 8 if cfg.num_levels == 4 else 2 ** (cfg.num_levels - 1)
     out = torch.empty((n, cfg.out_c, cfg.latent_h * scale, cfg.latent_w * scale), dtype=torch.float32, device="cuda")
-    dec.run(zd, packed, out)
+    if extrapolate is None:
+        dec.run(zd, packed, out)
+    else:
+        dec.run_extrapolated(zd, dev_latent(extrapolate[0], cfg), extrapolate[1], packed, out)
     torch.cuda.synchronize()
     res = out.cpu().numpy().astype(np.float64)
     dec.close()
@@ -133,9 +223,10 @@ def test_decoder_reduced_size(dtype):
     want = ref.decoder(z, weights, level_channels=chans, resblocks_per_level=2, groups=32, eps=1e-6)
     assert got.shape == want.shape == (3, 3, 56, 72)
     err = ref.rel_err(got, want)
-    # 20 convolutions deep: bf16 operands and storage accumulate beyond the single-stage bar (see the
-    # full-size test); f16 must meet it
-    assert err <= (G.TOL["f16"] if dtype == "f16" else 1e-1), err
+    # 20 convolutions deep: bf16 operand rounding (2^-9 relative per product term, independent from layer to layer)
+    # accumulates beyond the single-stage bar, see test_decoder_full_size_bf16; f16 must meet the bar.  bf16 measures
+    # 5.4e-2 here (random GroupNorm affine widens it); a broken path errs at order 1.
+    assert err <= (G.TOL["f16"] if dtype == "f16" else 8e-2), err
     # frames are independent: batched result == one-by-one result, bit for bit
     one = run_decoder(cfg, weights, z[1:2])
     assert np.array_equal(one[0], got[1])
@@ -228,25 +319,154 @@ def test_decoder_full_size_f16(workload4):
     assert np.array_equal(got, again)          # deterministic
 
 
-def test_decoder_full_size_bf16_reported(workload4):
-    """bf16 operands + bf16 storage through ~37 convolutions: forecast ~5e-2 of the output RMS, above the
-    2e-2 bar that f16 meets; asserted only against that forecast and printed."""
+@pytest.mark.xfail(strict=False, reason="bf16 MFMA operands through ~37 convolutions: measured 6.5e-2 of the output RMS "
+                   "against the 2e-2 bar (forecast with fp64 arithmetic and only the operand roundings injected: 3.0e-2 "
+                   "even with fp32 storage); the decoder's headline type is f16, which meets the bar")
+def test_decoder_full_size_bf16(workload4):
+    """The operand type the workload names, at the workload's bar.  Known not to meet it on the full decoder (the
+    per-stage workloads 2 and 3 do): every bf16 operand carries 2^-9 relative rounding error, independent from layer
+    to layer, and 37 layers of it exceed 2e-2 of the output RMS at the worst of a million outputs."""
     weights, z, want = workload4
     cfg = wmdec.decoder_default_config()
     cfg.act_dtype = wmdec.BF16
     got = run_decoder(cfg, weights, z)
     err = ref.rel_err(got, want)
     print("full decoder bf16: max|err|/rms = %.3e" % err)
-    assert err <= 1e-1, err
+    assert np.all(np.isfinite(got))
+    assert err <= G.TOL["bf16"], err
 
 
-def test_decoder_batched_workload5_properties():
-    """Workload 5: 4 temporally correlated latents.  Batched output equals frame-by-frame output bit for bit."""
-    weights = synth.decoder_weights(4)
+def test_decoder_full_size_bf16_stays_near_its_forecast(workload4):
+    """What bf16 does deliver on the full decoder: finite output, rms error below 1 % and worst-case error below the
+    1e-1 the rounding forecast allows (a broken bf16 path -- a wrong tile, a dropped tap -- errs at order 1)."""
+    weights, z, want = workload4
+    cfg = wmdec.decoder_default_config()
+    cfg.act_dtype = wmdec.BF16
+    got = run_decoder(cfg, weights, z)
+    rms = float(np.sqrt(np.mean(want * want)))
+    assert np.all(np.isfinite(got))
+    assert float(np.sqrt(np.mean((got - want) ** 2))) / rms <= 1.5e-2
+    assert ref.rel_err(got, want) <= 1e-1
+
+
+def test_f16_range_limit_is_visible_and_bf16_is_range_safe():
+    """f16 storage ends at 65504.  A latent 1e5 times larger than the workload's drives conv_in's output past that:
+    the f16 decoder must then return non-finite values (IEEE overflow to infinity, which GroupNorm turns into NaN
+    for the whole frame) -- never finite wrong ones -- while the bf16 decoder, whose range is fp32's, still agrees
+    with the oracle (GroupNorm makes the decoder scale-invariant after conv_in)."""
+    chans = (512, 128, 64, 32)
+    spec = synth.decoder_weight_spec(level_channels=chans, resblocks_per_level=2)
+    weights = synth.draw_params(spec, synth.weight_seed(9), random_affine=True)
+    z = synth.bf16_round(synth.latent_sequence(workload=9, frames=1, h=7, w=9) * 1e5)
+    got16 = run_decoder(small_cfg(wmdec.F16), weights, z)
+    assert not np.any(np.isfinite(got16)), "f16 overflow must poison the frame, not produce finite values"
+    gotb = run_decoder(small_cfg(wmdec.BF16), weights, z)
+    want = ref.decoder(z, weights, level_channels=chans, resblocks_per_level=2, groups=32, eps=1e-6)
+    assert np.all(np.isfinite(gotb))
+    assert ref.rel_err(gotb, want) <= 4e-2
+    # and at the workload's own scale the f16 activations stay far below the limit: the largest stored magnitude of
+    # a full-size run is checked in test_decoder_full_size_f16 through the finite, in-tolerance frame
+
+
+def test_decoder_batched_workload5(workload4):
+    """Workload 5: 4 temporally correlated latents z_t = z_0 + t*d + 0.1*eps_t through the decoder in one batch.
+    Every frame against the fp64 oracle, and the batched output equal to frame-by-frame output bit for bit."""
+    weights = workload4[0]
     z = synth.latent_sequence(5)
     cfg = wmdec.decoder_default_config()
     got = run_decoder(cfg, weights, z)
     assert got.shape == (4, 3, 480, 720) and np.all(np.isfinite(got))
+    for t in range(4):
+        want = ref.decoder(z[t:t + 1], weights)
+        err = ref.rel_err(got[t:t + 1], want)
+        print("workload 5 frame %d: max|err|/rms = %.3e" % (t, err))
+        assert err <= G.TOL["f16"], (t, err)
     for t in (0, 3):
         one = run_decoder(cfg, weights, z[t:t + 1])
         assert np.array_equal(one[0], got[t]), t
+
+
+def test_statistics_from_the_epilogue_match_the_statistics_pass():
+    """The moments a convolution emits for its own output replace the streaming pass over that output.  Both are
+    moments of the stored tensor and agree to fp32 accuracy (test_conv_epilogue_statistics compares them directly);
+    a relative change of 1e-7 in a scale still flips the 16-bit rounding of some stored activations, so the two
+    graphs are two realisations of the same rounding noise: each must meet the bar against the oracle, and their
+    difference stays at the size of that noise."""
+    chans = (512, 128, 64, 64)
+    spec = synth.decoder_weight_spec(level_channels=chans, resblocks_per_level=2)
+    weights = synth.draw_params(spec, synth.weight_seed(11), random_affine=True)
+    z = synth.latent_sequence(workload=11, frames=2, h=9, w=11)
+    outs = []
+    for separate in (0, 1):
+        cfg = small_cfg(wmdec.F16)
+        cfg.latent_h, cfg.latent_w = 9, 11
+        cfg.level_channels[3] = 64
+        cfg.separate_stats_pass = separate
+        outs.append(run_decoder(cfg, weights, z))
+    want = ref.decoder(z, weights, level_channels=chans, resblocks_per_level=2, groups=32, eps=1e-6)
+    assert ref.rel_err(outs[0], want) <= G.TOL["f16"] and ref.rel_err(outs[1], want) <= G.TOL["f16"]
+    assert ref.rel_err(outs[0], outs[1]) <= G.TOL["f16"], ref.rel_err(outs[0], outs[1])
+
+
+# ------------------------------------------------------------------ latent extrapolation in front of the decoder
+def test_extrapolated_run_equals_decode_of_the_explicit_sum_bitwise():
+    """decoder_run_extrapolated forms z + (j+1)*lambda*v while conv_in stages its input.  wmdec_latent_extrapolate
+    writes the same fp32 sum to memory; decoding that fp32 latent must give the same bits, frame by frame."""
+    cfg = small_cfg(wmdec.F16)
+    cfg.latent_dtype = wmdec.F32
+    chans = (512, 128, 64, 32)
+    spec = synth.decoder_weight_spec(level_channels=chans, resblocks_per_level=2)
+    weights = synth.draw_params(spec, synth.weight_seed(9), random_affine=True)
+    r = np.random.default_rng(synth.input_seed(12))
+    z = r.standard_normal((1, 4, 7, 9)).astype(np.float32)
+    v = (0.3 * r.standard_normal((1, 4, 7, 9))).astype(np.float32)
+    lam = 0.75
+    fused = run_decoder(cfg, weights, z, extrapolate=(v, lam, 3))
+    zd, vd = dev_latent(z, cfg), dev_latent(v, cfg)
+    for j in range(3):
+        zj = torch.empty_like(zd)
+        wmdec.latent_extrapolate(zd, vd, lam, j + 1, zj)
+        torch.cuda.synchronize()
+        want_z = ref.extrapolated_latents(z, v, lam, j + 1)[j]
+        assert np.max(np.abs(zj.cpu().numpy() - want_z)) <= 4e-7 * np.max(np.abs(want_z))
+        one = run_decoder(cfg, weights, zj.cpu().numpy())
+        assert np.array_equal(one[0], fused[j]), j
+
+
+@pytest.mark.parametrize("latent", ["bf16", "f32"])
+def test_extrapolated_run_against_the_oracle_reduced(latent):
+    """Alg. 2, hit branch, three consecutive hits: frame j = Decode(z after j+1 steps of z <- z + lambda*v), the oracle
+    iterating the recursion in fp64 and decoding every latent."""
+    cfg = small_cfg(wmdec.F16)
+    cfg.latent_dtype = G.ENUM[latent]
+    chans = (512, 128, 64, 32)
+    spec = synth.decoder_weight_spec(level_channels=chans, resblocks_per_level=2)
+    weights = synth.draw_params(spec, synth.weight_seed(9), random_affine=True)
+    seq = synth.latent_sequence(workload=12, frames=2, h=7, w=9)      # z_{t-2}, z_{t-1}
+    z, v = seq[1:2], synth.bf16_round(seq[1:2] - seq[0:1])            # motion vector as stored (bf16-representable)
+    lam = 0.5
+    got = run_decoder(cfg, weights, z, extrapolate=(v, lam, 3))
+    zs = ref.extrapolated_latents(z[0], v[0], lam, 3)
+    want = ref.decoder(zs, weights, level_channels=chans, resblocks_per_level=2, groups=32, eps=1e-6)
+    assert got.shape == want.shape == (3, 3, 56, 72)
+    assert ref.rel_err(got, want) <= G.TOL["f16"]
+    # lambda = 0: every frame is the decode of z itself
+    same = run_decoder(cfg, weights, z, extrapolate=(v, 0.0, 2))
+    plain = run_decoder(cfg, weights, z)
+    assert np.array_equal(same[0], plain[0]) and np.array_equal(same[1], plain[0])
+
+
+def test_extrapolated_run_full_size(workload4):
+    """Two extrapolated 720x480 frames from the workload's latents: z_{t-1} = frame 1 of workload 5's sequence, v its
+    difference to frame 0, lambda = 1 (what workload 5 imitates), against the oracle."""
+    weights = workload4[0]
+    seq = synth.latent_sequence(5)
+    z, v = seq[1:2], synth.bf16_round(seq[1:2] - seq[0:1])
+    cfg = wmdec.decoder_default_config()
+    got = run_decoder(cfg, weights, z, extrapolate=(v, 1.0, 2))
+    zs = ref.extrapolated_latents(z[0], v[0], 1.0, 2)
+    for j in range(2):
+        want = ref.decoder(zs[j:j + 1], weights)
+        err = ref.rel_err(got[j:j + 1], want)
+        print("extrapolated frame %d: max|err|/rms = %.3e" % (j, err))
+        assert err <= G.TOL["f16"], (j, err)
