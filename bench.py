@@ -18,17 +18,20 @@ sys.path.insert(0, ROOT)
 
 PEAK = {"mfma": 2516.6, "hbm": 8000.0}   # TFLOP/s dense bf16/f16 MFMA, GB/s HBM3E (published MI355X figures)
 
-# HBM traffic per launch (MB read, MB written) of the kernels that can dominate, averaged over their launches in one
-# frame: counter passes of this same command under rocprofv3, scaled by what the counters read for a plain copy of
-# known size.  Counters cannot be collected from inside this process; the passes are summarised under profiles/.
-PMC_TRAFFIC_MB = {
-    "conv_mfma_kernel<wmdec::f16_t, wmdec::f16_t, 8, 16, 1, 4, 1, 3, 32, 2, false>": (140.7, 33.3),
-    "conv_mfma_kernel<wmdec::f16_t, wmdec::f16_t, 8, 32, 2, 2, 2, 3, 32, 2, false>": (177.0, 89.6),
-    "conv_mfma_kernel<wmdec::f16_t, wmdec::f16_t, 8, 16, 4, 1, 2, 3, 32, 0, true>": (174.2, 96.3),
-    "conv_mfma_kernel<wmdec::f16_t, wmdec::f16_t, 8, 32, 2, 2, 2, 1, 64, 0, false>": (179.0, 66.4),
-    "conv_mfma_kernel<wmdec::f16_t, wmdec::f16_t, 8, 16, 2, 2, 2, 3, 32, 2, false>": (35.3, 5.6),
-    "flash_attn_kernel": (106.0, 33.3),
-}
+# HBM traffic per launch comes from two rocprofv3 counter passes of this same command (counters cannot be collected
+# from inside this process); their summary, written by `python -m paper_2602_00608_amd.profile_summary traffic`, is
+# read back here and used only if it was taken from the kernel sources this run was built from.
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "decoder_full_f16_hbm_traffic.md")
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def main():
@@ -49,7 +52,7 @@ def main():
 
     import numpy as np
     import torch
-    from paper_2602_00608_amd import synth, wmdec
+    from paper_2602_00608_amd import profile_summary, synth, wmdec
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
@@ -117,11 +120,17 @@ def main():
         achieved = d["bytes"] / (d["ms"] * 1e-3) / 1e9
         unit = "GB/s"
     traffic = traffic_detail = None   # HBM bytes per launch
-    if args.batch == 1 and args.dtype == "f16" and dom in PMC_TRAFFIC_MB:
-        fetch_mb, write_mb = PMC_TRAFFIC_MB[dom]
-        traffic = round((fetch_mb + write_mb) * 1e6)
+    digest, table = profile_summary.read_traffic_table(TRAFFIC_SUMMARY)
+    short = profile_summary.short_name(dom)
+    if args.batch == 1 and args.dtype == "f16" and short in table:
+        fetch_mb, write_mb = table[short]
+        current = digest == profile_summary.source_digest()
         traffic_detail = {"fetch_mb_per_launch": fetch_mb, "write_mb_per_launch": write_mb,
-                          "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes of this command, copy-calibrated (profiles/)"}
+                          "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes of this command, copy-calibrated "
+                                    "(profiles/decoder_full_f16_hbm_traffic.md)",
+                          "taken_from_these_kernel_sources": current}
+        if current:
+            traffic = round((fetch_mb + write_mb) * 1e6)
     roofline = {"kernel": dom, "bound": bound, "achieved": round(achieved, 2), "peak": PEAK[bound], "unit": unit,
                 "frac": round(achieved / PEAK[bound], 4), "traffic": traffic, "traffic_detail": traffic_detail,
                 "launches_per_step": d["launches"], "avg_launch_us": round(d["ms"] * 1e3 / d["launches"], 2),
@@ -143,7 +152,7 @@ def main():
         torch.cuda.synchronize()
         err = ref.rel_err(out[:1].cpu().numpy(), want)
         cpu = {"value": round(1.0 / dt, 5), "unit": "frames/s", "cores": os.cpu_count() if not os.environ.get("OMP_NUM_THREADS")
-               else int(os.environ["OMP_NUM_THREADS"]), "kind": "oracle",
+               else int(os.environ["OMP_NUM_THREADS"]), "cpu_model": cpu_model(), "kind": "oracle",
                "sample": "1 frame of the same workload (full decoder, fp64, %.1f s)" % dt,
                "gpu_vs_oracle_max_abs_err_over_rms": float("%.3e" % err)}
 
@@ -155,7 +164,9 @@ def main():
         "data": "synthetic",
         "config": {"workload": "configs[3]: full decoder, latent z[%d,4,60,90] -> frame [%d,3,480,720], batch %d"
                    % (args.batch, args.batch, args.batch), "frames_per_step": args.batch,
-                   "gflop_per_frame": round(dec.flops_per_frame() / 1e9, 1), "launches_per_step": dec.num_launches()},
+                   "gflop_per_frame": round(dec.flops_per_frame() / 1e9, 1),
+                   "gflop_per_frame_if_upsampling_convs_ran_nine_taps": round(dec.dense_flops_per_frame() / 1e9, 1),
+                   "launches_per_step": dec.num_launches()},
         "tflops": round(dec.flops_per_frame() * fps / 1e12, 1),
         "roofline": roofline, "cpu_baseline": cpu, "kernel_families": families}))
 

@@ -69,6 +69,24 @@ size_t wmdec_gn_stats_workspace_bytes(int n, int h, int w, int c, int groups);
 int wmdec_gn_stats(const void* x, int x_dtype, int n, int h, int w, int c, int groups, float eps,
                    float* mean, float* rstd, void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same statistics for callers that cannot allocate device memory or hand
+ * over a workspace (code under HIP-graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the partial moments and the ticket
+ * counters live in a file-scope device array of the library, 1 MiB + 256
+ * bytes per GPU, held until the process ends.  The call allocates nothing and
+ * enqueues kernels only (a small fill kernel puts the counters back to zero,
+ * then the statistics kernels of wmdec_gn_stats run on that array), so mean
+ * and rstd equal wmdec_gn_stats's bit for bit.
+ * Limits: n <= 64 and n * groups * slabs * 12 bytes <= 1 MiB, where slabs <=
+ * 256 for shapes of the single-launch layout (16-bit: c % 8 == 0, c/8 divides
+ * 1024, channels per group a power of two <= 64) and <= 2048 otherwise; e.g.
+ * every activation of the 720x480 decoder up to batch 10.  Beyond the limit:
+ * WMDEC_ERR_WORKSPACE and nothing is launched.
+ * All calls on one GPU share the array: calls that overlap in time on one GPU
+ * (different streams or threads) race; order them on one stream. */
+int wmdec_gn_stats_noalloc(const void* x, int x_dtype, int n, int h, int w, int c, int groups, float eps,
+                           float* mean, float* rstd, void* stream);
+
 /* ------------------------------------------------------------------------
  * Weight packing.  Convolution kernels read weights in a packed order: per
  * tap, fragments of 32 output x 16 input channels, each stored as 1 KiB (for

@@ -2,10 +2,16 @@
 
     python -m paper_2602_00608_amd.bench_ops [--dtype f16|bf16] [--reps 20]      (or run the file directly)
 
-Prints one line per operator: microseconds per call (HIP events around `reps` back-to-back calls on the current
-stream, inputs resident in HBM), algorithmic TFLOP/s or GB/s, and the fraction of the published MI355X peak
-(2516.6 TFLOP/s dense f16/bf16 MFMA, 8000 GB/s HBM).  Inputs are seeded N(0,1) tensors and 1/sqrt(fan_in)
-weights; real activations toggle fewer bits, so inside decoder_run the same convolutions run somewhat faster.
+Prints one line per operator: microseconds per call, algorithmic TFLOP/s or GB/s, and the fraction of the
+published MI355X peak (2516.6 TFLOP/s dense f16/bf16 MFMA, 8000 GB/s HBM).  Two timings per operator, both with HIP
+events on the current stream and inputs resident in HBM:
+  warm  `reps` back-to-back calls on the same tensors (tensors up to a few hundred MB partly stay in the last-level
+        cache between calls);
+  cold  between two calls a 2 GiB buffer is streamed (read and written), which evicts every cache level; the time
+        of the streaming kernel alone, measured the same way, is subtracted.
+An upsampling convolution that is evaluated per output phase is priced at the 2x2 taps it executes (4/9 of the
+nine-tap figure).  Inputs are seeded N(0,1) tensors and 1/sqrt(fan_in) weights; real activations toggle fewer bits,
+so inside decoder_run the same convolutions run somewhat faster.
 """
 import argparse
 import os
@@ -24,10 +30,7 @@ TORCH = {"f16": torch.float16, "bf16": torch.bfloat16}
 ENUM = {"f16": wmdec.F16, "bf16": wmdec.BF16}
 
 
-def timeit(fn, reps):
-    for _ in range(3):
-        fn()
-    torch.cuda.synchronize()
+def _events(fn, reps):
     t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0.record()
     for _ in range(reps):
@@ -35,6 +38,28 @@ def timeit(fn, reps):
     t1.record()
     torch.cuda.synchronize()
     return t0.elapsed_time(t1) / reps * 1e3   # microseconds
+
+
+def timeit(fn, reps):
+    """(warm, cold) microseconds per call."""
+    for _ in range(3):
+        fn()
+    torch.cuda.synchronize()
+    warm = _events(fn, reps)
+    creps = max(3, reps // 4)
+    flush = timeit.flush
+
+    def evict():
+        flush.add_(1)          # reads and writes 2 GiB: nothing of the operator's tensors survives in any cache
+
+    def cold_call():
+        evict()
+        fn()
+    evict()
+    torch.cuda.synchronize()
+    base = _events(evict, creps)
+    cold = _events(cold_call, creps) - base
+    return warm, cold
 
 
 def main():
@@ -45,6 +70,7 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench_ops: no GPU visible; the HIP path has no CPU fallback")
     torch.manual_seed(260200608)
+    timeit.flush = torch.zeros(2 << 30, dtype=torch.uint8, device="cuda")
     dt, en = TORCH[args.dtype], ENUM[args.dtype]
     groups, eps = 32, 1e-6
 
@@ -56,48 +82,64 @@ def main():
         wmdec.gn_stats(x, groups, eps, mean, rstd, ws)
         return mean, rstd, ws
 
-    # cin, cout, h_out, w_out, kernel, upsample
-    convs = [(128, 128, 480, 720, 3, 0), (256, 128, 480, 720, 3, 0), (256, 256, 240, 360, 3, 0), (512, 256, 240, 360, 3, 0),
-             (512, 512, 120, 180, 3, 0), (512, 512, 60, 90, 3, 0), (256, 256, 480, 720, 3, 1), (512, 512, 240, 360, 3, 1),
-             (512, 512, 120, 180, 3, 1), (256, 128, 480, 720, 1, 0), (512, 256, 240, 360, 1, 0), (512, 1536, 60, 90, 1, 0)]
-    for cin, cout, h, w, k, ups in convs:
+    def line(name, shape, us, work, unit, peak):
+        warm, cold = us
+        print("%-20s %-22s warm %8.1f us %8.1f %s (%4.1f%%)   cold %8.1f us %8.1f %s (%4.1f%% of %.0f)"
+              % (name, shape, warm, work / warm / 1e6 if unit == "TFLOP/s" else work / warm / 1e3, unit,
+                 (work / warm / 1e6 if unit == "TFLOP/s" else work / warm / 1e3) / peak * 100,
+                 cold, work / cold / 1e6 if unit == "TFLOP/s" else work / cold / 1e3, unit,
+                 (work / cold / 1e6 if unit == "TFLOP/s" else work / cold / 1e3) / peak * 100, peak), flush=True)
+
+    # cin, cout, h_out, w_out, kernel, upsample, normalise + SiLU on load, residual
+    convs = [(128, 128, 480, 720, 3, 0, 1, 1), (256, 128, 480, 720, 3, 0, 1, 0), (256, 256, 240, 360, 3, 0, 1, 1),
+             (512, 256, 240, 360, 3, 0, 1, 0), (512, 512, 120, 180, 3, 0, 1, 1), (512, 512, 60, 90, 3, 0, 1, 1),
+             (256, 256, 480, 720, 3, 1, 0, 0), (512, 512, 240, 360, 3, 1, 0, 0), (512, 512, 120, 180, 3, 1, 0, 0),
+             (256, 128, 480, 720, 1, 0, 0, 0), (512, 256, 240, 360, 1, 0, 0, 0), (512, 1536, 60, 90, 1, 0, 1, 0),
+             (128, 3, 480, 720, 3, 0, 1, 0)]
+    for cin, cout, h, w, k, ups, norm, use_res in convs:
         hi, wi = (h // 2, w // 2) if ups else (h, w)
+        out_dt = torch.float32 if cout == 3 else dt          # conv_out writes the fp32 frame
         x = torch.randn((1, hi, wi, cin), device="cuda").to(dt)
-        y = torch.empty((1, h, w, cout), device="cuda", dtype=dt)
-        res = torch.randn((1, h, w, cout), device="cuda").to(dt)
+        y = torch.empty((1, h, w, cout), device="cuda", dtype=out_dt)
+        res = torch.randn((1, h, w, cout), device="cuda").to(dt) if use_res else None
         wsrc = torch.randn((cout, cin, k, k), device="cuda") / (cin * k * k) ** 0.5
         bias = 0.01 * torch.randn(cout, device="cuda")
         gamma, beta = torch.ones(cin, device="cuda"), torch.zeros(cin, device="cuda")
+        flops = 2.0 * k * k * cin * cout * h * w
+        nbytes = x.numel() * 2 + y.numel() * y.element_size() + (res.numel() * 2 if use_res else 0) + wsrc.numel() * 2
         if ups:
             wp = torch.empty(wmdec.upconv_packed_bytes(cout, cin, en), dtype=torch.uint8, device="cuda")
             wmdec.pack_upconv_weights(wsrc, wp, en)
             us = timeit(lambda: wmdec.upsample2x_conv3x3(x, wp, bias, y), args.reps)
             name = "upsample2x_conv3x3"
+            if args.dtype == "f16" and cout % 64 == 0:
+                flops *= 4.0 / 9.0        # evaluated per output phase: 2x2 taps executed
         else:
             wp = torch.empty(wmdec.conv_packed_bytes(cout, cin, k, en), dtype=torch.uint8, device="cuda")
             wmdec.pack_conv_weights(wsrc, wp, en)
             mean, rstd, _ = stats_of(x)
             fn = wmdec.gn_silu_conv3x3 if k == 3 else wmdec.gn_conv1x1
-            us = timeit(lambda: fn(x, mean, rstd, gamma, beta, groups, True, wp, bias, res, y), args.reps)
+            if norm:
+                us = timeit(lambda: fn(x, mean, rstd, gamma, beta, groups, True, wp, bias, res, y), args.reps)
+            else:
+                us = timeit(lambda: fn(x, None, None, None, None, groups, False, wp, bias, res, y), args.reps)
             name = "gn_silu_conv3x3" if k == 3 else "gn_conv1x1"
-        flops = 2.0 * k * k * cin * cout * h * w
-        print("%-20s %4d->%4d @%3dx%3d: %8.1f us  %7.1f TFLOP/s  (%4.1f%% of %.1f)"
-              % (name, cin, cout, h, w, us, flops / us / 1e6, flops / us / 1e6 / PEAK_TFLOPS * 100, PEAK_TFLOPS), flush=True)
+        shape = "%4d->%4d @%3dx%3d" % (cin, cout, h, w)
+        if flops / nbytes >= 315:            # above the ridge point: priced against the matrix cores
+            line(name, shape, us, flops, "TFLOP/s", PEAK_TFLOPS)
+        else:
+            line(name, shape, us, nbytes, "GB/s", PEAK_GBPS)
 
     for c, h, w in [(128, 480, 720), (256, 480, 720), (256, 240, 360), (512, 120, 180), (512, 60, 90)]:
         x = torch.randn((1, h, w, c), device="cuda").to(dt)
         mean, rstd, ws = stats_of(x)
         us = timeit(lambda: wmdec.gn_stats(x, groups, eps, mean, rstd, ws), args.reps)
-        nbytes = x.numel() * 2
-        print("%-20s %4d       @%3dx%3d: %8.1f us  %7.1f GB/s    (%4.1f%% of %.0f)"
-              % ("gn_stats", c, h, w, us, nbytes / us / 1e3, nbytes / us / 1e3 / PEAK_GBPS * 100, PEAK_GBPS), flush=True)
+        line("gn_stats", "%4d       @%3dx%3d" % (c, h, w), us, x.numel() * 2, "GB/s", PEAK_GBPS)
 
     x = torch.randn((1, 120, 180, 256), device="cuda").to(dt)
     y = torch.empty((1, 240, 360, 256), device="cuda", dtype=dt)
     us = timeit(lambda: wmdec.upsample2x_nearest(x, y), args.reps)
-    nbytes = (x.numel() + y.numel()) * 2
-    print("%-20s %4d       @%3dx%3d: %8.1f us  %7.1f GB/s    (%4.1f%% of %.0f)"
-          % ("upsample2x_nearest", 256, 240, 360, us, nbytes / us / 1e3, nbytes / us / 1e3 / PEAK_GBPS * 100, PEAK_GBPS), flush=True)
+    line("upsample2x_nearest", "%4d       @%3dx%3d" % (256, 240, 360), us, (x.numel() + y.numel()) * 2, "GB/s", PEAK_GBPS)
 
 
 if __name__ == "__main__":

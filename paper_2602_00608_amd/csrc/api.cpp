@@ -394,6 +394,17 @@ int wmdec_gn_stats(const void* x, int x_dtype, int n, int h, int w, int c, int g
                          workspace_bytes - head, (hipStream_t)stream);
 }
 
+int wmdec_gn_stats_noalloc(const void* x, int x_dtype, int n, int h, int w, int c, int groups, float eps, float* mean,
+                           float* rstd, void* stream) {
+  WMDEC_REQUIRE(x && mean && rstd, WMDEC_ERR_INVALID_ARG, "gn_stats_noalloc: null pointer");
+  WMDEC_REQUIRE(valid_dtype(x_dtype), WMDEC_ERR_INVALID_ARG, "gn_stats_noalloc: bad dtype %d", x_dtype);
+  WMDEC_REQUIRE(n > 0 && h > 0 && w > 0 && c > 0 && groups > 0, WMDEC_ERR_INVALID_ARG, "gn_stats_noalloc: non-positive size");
+  WMDEC_REQUIRE(c % groups == 0, WMDEC_ERR_SHAPE, "gn_stats_noalloc: c %d not divisible by groups %d", c, groups);
+  WMDEC_REQUIRE(eps >= 0.f, WMDEC_ERR_INVALID_ARG, "gn_stats_noalloc: negative eps");
+  WMDEC_REQUIRE(aligned16(x), WMDEC_ERR_INVALID_ARG, "gn_stats_noalloc: x must be 16-byte aligned");
+  return launch_gn_stats_static(x, x_dtype, n, h, w, c, groups, eps, mean, rstd, (hipStream_t)stream);
+}
+
 size_t wmdec_conv_packed_bytes(int cout, int cin, int k, int op_dtype) {
   if (cout <= 0 || cin <= 0 || (k != 1 && k != 3) || !valid_dtype(op_dtype)) return 0;
   return packed_elems(k * k, cout, cin) * dtype_size(op_dtype);

@@ -122,6 +122,10 @@ int gn_stats_num_launches(int x_dtype, int h, int w, int c, int groups);   // 1:
 int launch_gn_stats(const void* x, int x_dtype, int n, int h, int w, int c, int groups, float eps,
                     float* mean, float* rstd, unsigned* ticket, void* moments, size_t moments_bytes, hipStream_t s);
 
+// same statistics with the library's built-in scratch (a file-scope device array) instead of a caller workspace
+int launch_gn_stats_static(const void* x, int x_dtype, int n, int h, int w, int c, int groups, float eps,
+                           float* mean, float* rstd, hipStream_t s);
+
 // merges `slots` moment triples per (sample, group) from ws[n_groups][slots] into mean / rstd
 int launch_gn_finalize(const void* ws, int n_groups, int slots, float eps, float* mean, float* rstd, hipStream_t s);
 

@@ -18,6 +18,8 @@
 // across the XCDs; the publishing wavefront waits until the memory system has acknowledged its stores (vmcnt = 0)
 // before it takes the ticket, and only the workgroup that draws the last ticket reads.  Under the language memory
 // model the relaxed accesses alone would not order the stores before the ticket; the wait does, on this hardware.
+#include <mutex>
+
 #include "moments.hpp"
 
 #if defined(__HIP_DEVICE_COMPILE__) && !defined(__gfx950__)
@@ -311,6 +313,45 @@ int launch_gn_stats(const void* x, int x_dtype, int n, int h, int w, int c, int 
   hipLaunchKernelGGL(gn_finalize, dim3((unsigned)(n * groups)), dim3(kFinThreads), 0, s, wsm, p.chunks, eps, mean, rstd);
   WMDEC_HIP(hipGetLastError());
   return WMDEC_OK;
+}
+
+// ---- the variant for callers that cannot allocate: the workspace is a file-scope device array
+constexpr size_t kStaticTicketBytes = 256;                 // 64 ticket counters
+constexpr size_t kStaticMomentsBytes = (size_t)1 << 20;    // 87381 moment triples
+static __device__ __align__(256) unsigned char scratch[kStaticTicketBytes + kStaticMomentsBytes];
+
+size_t gn_stats_static_capacity_bytes() { return kStaticMomentsBytes; }
+
+int launch_gn_stats_static(const void* x, int x_dtype, int n, int h, int w, int c, int groups, float eps,
+                           float* mean, float* rstd, hipStream_t s) {
+  const Plan p = make_plan(x_dtype, n, h, w, c, groups);
+  const size_t need = (size_t)n * groups * p.chunks * sizeof(Moments);
+  WMDEC_REQUIRE((size_t)n * sizeof(unsigned) <= kStaticTicketBytes && need <= kStaticMomentsBytes, WMDEC_ERR_WORKSPACE,
+                "gn_stats_noalloc: %d samples x %d groups x %d slabs need %zu bytes of built-in scratch, the limit is %zu "
+                "(and 64 samples); use wmdec_gn_stats with a workspace", n, groups, p.chunks, need, kStaticMomentsBytes);
+  // every device holds its own copy of the array at its own address: resolve it once per device, with that device current
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static unsigned char* dev_scratch[kMaxDevices] = {};
+  int dev = -1;
+  WMDEC_HIP(hipGetDevice(&dev));
+  WMDEC_REQUIRE(dev >= 0 && dev < kMaxDevices, WMDEC_ERR_UNSUPPORTED, "gn_stats_noalloc: device index %d not supported", dev);
+  unsigned char* ptr;
+  {
+    std::lock_guard<std::mutex> lock(mu);
+    if (!dev_scratch[dev]) {
+      void* sym = nullptr;
+      WMDEC_HIP(hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)));
+      dev_scratch[dev] = (unsigned char*)sym;
+    }
+    ptr = dev_scratch[dev];
+  }
+  // the array keeps what the last call left: the counters are put back to zero by a fill kernel (not a memset
+  // node: the call may be captured in a graph); the moment slots are all written before they are read
+  const int rc = launch_zero_u32(ptr, (int)(kStaticTicketBytes / sizeof(unsigned)), s);
+  if (rc != WMDEC_OK) return rc;
+  return launch_gn_stats(x, x_dtype, n, h, w, c, groups, eps, mean, rstd, (unsigned*)ptr, ptr + kStaticTicketBytes,
+                         kStaticMomentsBytes, s);
 }
 
 }  // namespace wmdec

@@ -40,6 +40,7 @@ SIGNATURES = {
     "wmdec_status_string": (ctypes.c_char_p, [_i]),
     "wmdec_gn_stats_workspace_bytes": (_sz, [_i] * 5),
     "wmdec_gn_stats": (_i, [_vp, _i, _i, _i, _i, _i, _i, _f, _vp, _vp, _vp, _sz, _vp]),
+    "wmdec_gn_stats_noalloc": (_i, [_vp, _i, _i, _i, _i, _i, _i, _f, _vp, _vp, _vp]),
     "wmdec_conv_packed_bytes": (_sz, [_i] * 4),
     "wmdec_pack_conv_weights": (_i, [_vp, _i, _i, _i, _i, _vp, _i, _vp]),
     "wmdec_gn_silu_conv3x3": (_i, [_vp, _i, _vp, _vp, _vp, _vp, _i, _i, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp]),
@@ -134,6 +135,12 @@ def gn_stats(x, groups, eps, mean, rstd, workspace):
     n, h, w, c = x.shape
     _check(lib().wmdec_gn_stats(_ptr(x), dtype_enum(x), n, h, w, c, groups, eps, _ptr(mean), _ptr(rstd),
                                 _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def gn_stats_noalloc(x, groups, eps, mean, rstd):
+    """gn_stats on the library's built-in scratch: no workspace argument, no allocation."""
+    n, h, w, c = x.shape
+    _check(lib().wmdec_gn_stats_noalloc(_ptr(x), dtype_enum(x), n, h, w, c, groups, eps, _ptr(mean), _ptr(rstd), _stream()))
 
 
 def conv_packed_bytes(cout, cin, k, op_dtype):

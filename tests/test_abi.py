@@ -129,6 +129,25 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert l.wmdec_upconv_packed_bytes(64, 64, 9) == 0
     assert l.wmdec_pack_upconv_weights(p, wmdec.F16, 64, 64, 2 * p, wmdec.F16, None) == wmdec.ERR_INVALID_ARG   # source type
     assert l.wmdec_pack_upconv_weights(p, wmdec.F32, 64, 64, 2 * p + 8, wmdec.F16, None) == wmdec.ERR_INVALID_ARG   # alignment
+    # statistics on the built-in scratch: same argument checks, no workspace argument
+    assert l.wmdec_gn_stats_noalloc(None, 0, 1, 1, 1, 32, 32, 1e-6, None, None, None) == wmdec.ERR_INVALID_ARG
+    assert l.wmdec_gn_stats_noalloc(p, 0, 1, 4, 4, 30, 32, 1e-6, p, p, None) == wmdec.ERR_SHAPE
+    assert l.wmdec_gn_stats_noalloc(p, 1, 65, 2, 2, 32, 32, 1e-6, p, p, None) == wmdec.ERR_WORKSPACE
+    assert b"limit" in l.wmdec_last_error()
+    # convolution that also emits the moments of its output
+    assert l.wmdec_conv_stats_workspace_bytes(wmdec.F16, wmdec.F16, 1, 480, 720, 128, 128, 32) == 32 * 60 * 23 * 2 * 12
+    assert l.wmdec_conv_stats_workspace_bytes(wmdec.F32, wmdec.F32, 1, 8, 8, 64, 64, 32) == 0
+    assert l.wmdec_gn_silu_conv3x3_stats(p, 2, None, None, None, None, 32, 0, p, None, None, 2 * p, 2, 1, 8, 8, 64, 64,
+                                         24, 1e-6, p, p, p, 1 << 20, None) == wmdec.ERR_SHAPE
+    assert l.wmdec_gn_silu_conv3x3_stats(p, 2, None, None, None, None, 32, 0, p, None, None, 2 * p, 2, 1, 8, 8, 64, 64,
+                                         32, 1e-6, p, p, p, 16, None) == wmdec.ERR_WORKSPACE
+    assert l.wmdec_gn_silu_conv3x3_stats(p, 0, None, None, None, None, 32, 0, p, None, None, 2 * p, 0, 1, 8, 8, 64, 64,
+                                         32, 1e-6, p, p, p, 1 << 20, None) == wmdec.ERR_UNSUPPORTED
+    # latent extrapolation
+    assert l.wmdec_latent_extrapolate(p, None, 1, 0.5, 1, p, 1, 16, None) == wmdec.ERR_INVALID_ARG
+    assert l.wmdec_latent_extrapolate(p, p, 1, float("nan"), 1, p, 1, 16, None) == wmdec.ERR_INVALID_ARG
+    assert l.wmdec_latent_extrapolate(p, p, 1, 0.5, -1, p, 1, 16, None) == wmdec.ERR_INVALID_ARG
+    assert l.wmdec_latent_extrapolate(p, p, 1, 0.5, 1, p, 1, 0, None) == wmdec.OK          # nothing to do
     assert l.wmdec_status_string(wmdec.ERR_WORKSPACE) == b"workspace missing or too small"
     cfg = wmdec.decoder_default_config()
     cfg.level_channels[2] = 250
@@ -140,6 +159,9 @@ def test_argument_errors_are_reported_without_a_gpu():
     dec = wmdec.Decoder()
     assert l.decoder_run(dec.handle, p, p, p, 9, None) == wmdec.ERR_INVALID_ARG
     assert l.decoder_run(dec.handle, p, p, p, 1, None) == wmdec.ERR_WORKSPACE
+    assert l.decoder_run_extrapolated(dec.handle, p, None, 0.5, p, p, 1, None) == wmdec.ERR_INVALID_ARG
+    assert l.decoder_run_extrapolated(dec.handle, p, p, float("inf"), p, p, 1, None) == wmdec.ERR_INVALID_ARG
+    assert l.decoder_run_extrapolated(dec.handle, p, p, 0.5, p, p, 1, None) == wmdec.ERR_WORKSPACE
     ms = ctypes.c_float()
     assert l.decoder_time_step(dec.handle, p, p, p, 1, 0, 1, ctypes.byref(ms), None) == wmdec.ERR_INVALID_ARG   # no run yet
     assert l.decoder_time_step(dec.handle, p, p, p, 1, 999, 1, ctypes.byref(ms), None) == wmdec.ERR_INVALID_ARG
