@@ -246,7 +246,7 @@ __device__ __forceinline__ u32x4 load_fragment(__amdgpu_buffer_rsrc_t rsrc, int 
 // and each k-step pays a full memory latency.
 // VALU_PER_MFMA: -1 pins the order as written (slot hook after the MFMAs of an M tile); >= 0 asks the scheduler to
 // interleave that many vector-ALU instructions behind every MFMA of a k-step.
-template <typename T, int MI, int NI, int KS, int KC, int HW_, int PS, int D, bool SLICED, int VALU_PER_MFMA, typename Slice>
+template <typename T, int MI, int NI, int KS, int KC, int ROW, int PS, int D, bool SLICED, int VALU_PER_MFMA, typename Slice>
 __device__ __forceinline__ void mfma_chunk(const T* buf, const int (&a_off)[MI], __amdgpu_buffer_rsrc_t wrsrc, int bcur, int bnext,
                                            int tap_stride, int kk_stride, int lane16, u32x4 (&bq)[D][NI],
                                            f32x16 (&acc)[MI][NI], Slice&& slice) {
@@ -273,7 +273,7 @@ __device__ __forceinline__ void mfma_chunk(const T* buf, const int (&a_off)[MI],
       for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = Mma<T>::m32(af[mi], bq[s % D][ni], acc[mi][ni]);
       if constexpr (s + 1 < STEPS) {
         constexpr int tap = (s + 1) / KK, kk = (s + 1) % KK;
-        af[mi] = *reinterpret_cast<const u32x4*>(buf + a_off[mi] + ((tap / KS) * HW_ + tap % KS) * PS + kk * 16);
+        af[mi] = *reinterpret_cast<const u32x4*>(buf + a_off[mi] + (tap / KS) * ROW + (tap % KS) * PS + kk * 16);
       }
       if constexpr (SLICED) slice(std::integral_constant<int, s * MI + mi>{});
       if constexpr (VALU_PER_MFMA < 0) __builtin_amdgcn_sched_barrier(0);
@@ -308,9 +308,18 @@ constexpr int resident_workgroups(int acc_tiles, int wm, int wn) {
   return wm * wn == 8 ? 1 : (acc_tiles <= 4 && !(wm == 2 && wn == 2) ? 3 : 2);
 }
 
-// Pixel slots of a staged tile: every thread stores all its NV vectors, and at least one slot behind the patch is
-// spare: vectors that lie outside the image (or past the patch) are stored there, where no MFMA reads them.
-constexpr int tile_pixel_slots(int stored, int hp) { return stored > hp ? stored : hp + 1; }
+// LDS layout of a staged tile (elements of the 16-bit type): pixel (hy, hx) of the halo patch sits at hy * ROW + hx * PS.
+// PS = KC + 8: the 16-byte pad makes the 16 lanes that the LDS serves per cycle (consecutive pixels of a row, 16 bytes
+// each) fall on 64 distinct banks.  A 32-pixel M tile that spans two patch rows (16-pixel-wide patches) has lanes i and
+// i + 16 one row apart; the LDS only runs at full rate when such lane pairs are a multiple of 256 bytes apart (measured:
+// any other row stride costs a second pass per read), so for those patches the row stride is rounded up to 256 bytes.
+// One pixel slot behind the patch is spare: vectors that lie outside the image (or past the patch) are stored there,
+// where no MFMA reads them.
+constexpr int tile_row_elems(int tw, int pad, int kc) {
+  const int raw = (tw + 2 * pad) * (kc + 8);
+  return tw < 32 ? (raw * 2 + 255) / 256 * 128 : raw;
+}
+constexpr int tile_buf_elems(int th, int tw, int pad, int kc) { return (th + 2 * pad) * tile_row_elems(tw, pad, kc) + (kc + 8); }
 
 template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC, int ACT, bool PH = false>
 __global__ __launch_bounds__(64 * WM * WN, resident_workgroups(wave_m_tiles(TH, TW, WM, PH) * NI, WM, WN))
@@ -327,13 +336,15 @@ void conv_mfma_kernel(MfmaParams p) {
   constexpr int TN = WN * NI * 32;
   constexpr int VPP = KC / 8;                    // 16-byte vectors per pixel per chunk
   constexpr int NV = (HP * VPP + NT - 1) / NT;   // vectors a thread stages per chunk
-  constexpr int BUF = tile_pixel_slots(NV * NT / VPP, HP) * PS;   // elements of one staged tile: the halo patch plus spare pixel slots
+  constexpr int ROW = tile_row_elems(TW, PAD, KC);       // LDS row stride of the staged tile, elements
+  constexpr int BUF = tile_buf_elems(TH, TW, PAD, KC);   // elements of one staged tile: the halo patch plus the spare slot
+  constexpr int SPARE = HH_ * ROW;                       // element offset of the spare pixel slot
   constexpr int STEPS = KT * KT * (KC / 16), SLOTS = STEPS * MI;
   constexpr bool SLICED = KS == 3;               // activation of the next chunk is sliced into the MFMA sweep
   static_assert(NT % VPP == 0, "a thread keeps one channel octet");
 
   extern __shared__ __align__(16) unsigned char smem[];
-  T* s_a = reinterpret_cast<T*>(smem);                                          // [2][HP][PS]
+  T* s_a = reinterpret_cast<T*>(smem);                                          // [2][BUF]
   float2* s_ab = reinterpret_cast<float2*>(smem + ((2 * BUF * 2 + 15) & ~15));  // [cin] (scale, shift)
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -371,7 +382,7 @@ void conv_mfma_kernel(MfmaParams p) {
   for (int mi = 0; mi < MI; ++mi) {
     const int mt = PH ? mi : wm * MI + mi;
     const int ty = (mt / MT_PER_ROW) * MTH + lm / MTW, tx = (mt % MT_PER_ROW) * MTW + lm % MTW;
-    a_off[mi] = (ty * HW_ + tx) * PS + 8 * lk + (PH ? ((wave >> 1) * HW_ + (wave & 1)) * PS : 0);
+    a_off[mi] = ty * ROW + tx * PS + 8 * lk + (PH ? (wave >> 1) * ROW + (wave & 1) * PS : 0);
   }
   constexpr int KK = KC / 16;
   constexpr int D = prefetch_ring(KT * KT * KK, MI * NI);   // weight fragments are fetched D-1 k-steps ahead
@@ -410,10 +421,10 @@ void conv_mfma_kernel(MfmaParams p) {
       src_off[i] = ((sy * w_in + sx) * p.cin + cvec * 8) * (int)sizeof(T);
     }
     const bool keep = KS == 1 ? in_patch : inside;
-    dst_off[i] = (keep ? hp : HP) * PS + cvec * 8;
+    dst_off[i] = (keep ? hy * ROW + hx * PS : SPARE) + cvec * 8;
     if (KS != 1 && in_patch && !inside) {
-      *reinterpret_cast<u32x4*>(s_a + hp * PS + cvec * 8) = u32x4{0u, 0u, 0u, 0u};
-      *reinterpret_cast<u32x4*>(s_a + BUF + hp * PS + cvec * 8) = u32x4{0u, 0u, 0u, 0u};
+      *reinterpret_cast<u32x4*>(s_a + hy * ROW + hx * PS + cvec * 8) = u32x4{0u, 0u, 0u, 0u};
+      *reinterpret_cast<u32x4*>(s_a + BUF + hy * ROW + hx * PS + cvec * 8) = u32x4{0u, 0u, 0u, 0u};
     }
   }
   // One register set of raw vectors.  The loads of chunk k+1 are issued right after the MFMA sweep of chunk
@@ -510,10 +521,10 @@ void conv_mfma_kernel(MfmaParams p) {
       };
       // the last chunk activates a harmless reload into the buffer nobody reads: one instruction stream, no
       // control flow inside the pinned schedule
-      mfma_chunk<T, MI, NI, KT, KC, HW_, PS, D, true, SPREAD>(buf, a_off, wrsrc, bcur, bnext, tap_stride, kk_stride, lane16, bq, acc, slice);
+      mfma_chunk<T, MI, NI, KT, KC, ROW, PS, D, true, SPREAD>(buf, a_off, wrsrc, bcur, bnext, tap_stride, kk_stride, lane16, bq, acc, slice);
     } else {
       auto none = [](auto) {};
-      mfma_chunk<T, MI, NI, KT, KC, HW_, PS, D, false, -1>(buf, a_off, wrsrc, bcur, bnext, tap_stride, kk_stride, lane16, bq, acc, none);
+      mfma_chunk<T, MI, NI, KT, KC, ROW, PS, D, false, -1>(buf, a_off, wrsrc, bcur, bnext, tap_stride, kk_stride, lane16, bq, acc, none);
       if (more) activate_all(c0n, nbuf);
     }
     issue(c + 2);
@@ -539,7 +550,6 @@ void conv_mfma_kernel(MfmaParams p) {
 template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC, bool PH = false>
 int launch_cfg(const ConvArgs& a, hipStream_t s) {
   constexpr int PAD = PH ? 1 : KS / 2;
-  constexpr int HP = (TW + 2 * PAD) * (TH + 2 * PAD);
   constexpr int TN = WN * NI * 32;
   WMDEC_REQUIRE(!PH || (a.wt_phase && a.h % 2 == 0 && a.w % 2 == 0), WMDEC_ERR_INVALID_ARG, "conv_mfma: upsampling convolution without phase weights");
   MfmaParams p;
@@ -555,8 +565,7 @@ int launch_cfg(const ConvArgs& a, hipStream_t s) {
   p.stats = (Moments*)a.stats_ws; p.stats_groups = a.stats_groups; p.stats_cpg = a.stats_groups > 0 ? a.cout / a.stats_groups : 1;
   p.stats_slots = p.tiles_x * p.tiles_y * WM;
   constexpr int NT = 64 * WM * WN;
-  constexpr int NV = (HP * (KC / 8) + NT - 1) / NT;
-  size_t smem = (((size_t)2 * tile_pixel_slots(NV * NT / (KC / 8), HP) * (KC + 8) * 2 + 15) & ~(size_t)15) + (size_t)a.cin * sizeof(float2);
+  size_t smem = (((size_t)2 * tile_buf_elems(TH, TW, PAD, KC) * 2 + 15) & ~(size_t)15) + (size_t)a.cin * sizeof(float2);
   const size_t patch = (size_t)(WM * WN) * patch_floats(NI) * sizeof(float);   // epilogue patches of the wavefronts
   if (smem < patch) smem = patch;
   WMDEC_REQUIRE(smem <= 80 * 1024, WMDEC_ERR_UNSUPPORTED, "conv_mfma: %zu bytes of LDS needed", smem);
