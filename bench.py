@@ -43,6 +43,11 @@ def main():
     ap.add_argument("--dtype", default="f16", choices=["f16", "bf16"],
                     help="storage / MFMA operand type of activations (weights and latents are given in bf16)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--separate-stats", action="store_true",
+                    help="ablation: every GroupNorm runs the streaming statistics pass instead of taking the moments from "
+                         "the producing convolution's epilogue")
+    ap.add_argument("--separate-shortcut", action="store_true",
+                    help="ablation: the 1x1 shortcuts are launches of their own instead of contraction steps of conv2")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="first copy 256 MiB device to device three times: a kernel of known traffic for counter passes")
     args = ap.parse_args()
@@ -70,6 +75,8 @@ def main():
     cfg = wmdec.decoder_default_config()
     cfg.act_dtype = wmdec.F16 if args.dtype == "f16" else wmdec.BF16
     cfg.max_batch = max(4, args.batch)
+    cfg.separate_stats_pass = int(args.separate_stats)
+    cfg.separate_shortcut = int(args.separate_shortcut)
     dec = wmdec.Decoder(cfg)
     weights = synth.decoder_weights(4)
     blob = np.zeros(dec.weights_bytes(), np.uint8)
@@ -166,7 +173,9 @@ def main():
                    % (args.batch, args.batch, args.batch), "frames_per_step": args.batch,
                    "gflop_per_frame": round(dec.flops_per_frame() / 1e9, 1),
                    "gflop_per_frame_if_upsampling_convs_ran_nine_taps": round(dec.dense_flops_per_frame() / 1e9, 1),
-                   "launches_per_step": dec.num_launches()},
+                   "launches_per_step": dec.num_launches(),
+                   "graph": {"statistics": "separate pass" if args.separate_stats else "from the producer's epilogue",
+                             "shortcut": "separate launch" if args.separate_shortcut else "folded into conv2"}},
         "tflops": round(dec.flops_per_frame() * fps / 1e12, 1),
         "roofline": roofline, "cpu_baseline": cpu, "kernel_families": families}))
 

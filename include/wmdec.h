@@ -140,6 +140,23 @@ int wmdec_gn_silu_conv3x3_stats(const void* x, int act_dtype, const float* mean,
                                 int out_groups, float out_eps, float* mean_out, float* rstd_out,
                                 void* workspace, size_t workspace_bytes, void* stream);
 
+/* Second convolution of a channel-changing ResBlock with the block's 1x1
+ * shortcut folded into its contraction (the Eq. 9 accounting applied to
+ * S(x) + conv3x3(...): the shortcut tensor is neither written nor read back):
+ *   y = bias + conv3x3(u) + bias2 + W2 * x2,   u as above,
+ * i.e. a contraction over K = 9*cin + cin2.  x2: [n,h,w,cin2] of act_dtype, taken
+ * as stored (no normalisation); w2_packed: [cout][cin2] packed with k = 1; bias2
+ * fp32 [cout] or NULL.  x2 and y must not overlap.  Shapes the matrix-core
+ * kernel takes (16-bit types, cin % 32 == 0, cin2 % 32 == 0, cout % 64 == 0) run
+ * as one launch; anything else (and F32) as two launches of the general kernel,
+ * the second adding the shortcut it finds in y. */
+int wmdec_gn_silu_conv3x3_shortcut(const void* x, int act_dtype, const float* mean, const float* rstd,
+                                   const float* gamma, const float* beta, int groups, int apply_silu,
+                                   const void* w_packed, const float* bias,
+                                   const void* x2, int cin2, const void* w2_packed, const float* bias2,
+                                   void* y, int y_dtype, int n, int h, int w, int cin, int cout,
+                                   void* stream);
+
 /* 1x1 convolution (a GEMM over pixels; the workload's attention projections
  * q, k, v, proj and the 1x1 shortcut of a channel-changing ResBlock -- the
  * "plus a residual" of the ResBlock when C_in != C_out) with the same optional
@@ -237,10 +254,13 @@ typedef struct {
   int separate_stats_pass;          /* 0: a GroupNorm takes its statistics from the epilogue of the convolution that
                                        produced its input (no extra read of the tensor); 1: every GroupNorm runs the
                                        streaming statistics pass (wmdec_gn_stats) -- the graph before that fusion */
+  int separate_shortcut;            /* 0: the 1x1 shortcut of a channel-changing ResBlock is folded into the contraction
+                                       of the block's second convolution; 1: it is a launch of its own whose output the
+                                       second convolution adds -- the graph before that fusion */
 } wmdec_decoder_config;
 
 /* Fills *cfg with the 720x480 decoder above (act_dtype = WMDEC_F16, max_batch = 4,
- * latent_dtype = WMDEC_BF16, separate_stats_pass = 0). */
+ * latent_dtype = WMDEC_BF16, separate_stats_pass = 0, separate_shortcut = 0). */
 void decoder_default_config(wmdec_decoder_config* cfg);
 
 /* Validates cfg and builds the host-side plan.  Allocates no device memory. */

@@ -29,6 +29,7 @@ int hip_fail(hipError_t e, const char* what) {
 
 int launch_conv(const ConvArgs& a, hipStream_t s) {
   if (conv_mfma_supported(a)) return launch_conv_mfma(a, s);
+  WMDEC_REQUIRE(!a.x2, WMDEC_ERR_UNSUPPORTED, "conv: only the matrix-core kernel folds a shortcut into the contraction");
   if (conv_small_cin_supported(a)) return launch_conv_small_cin(a, s);
   return launch_conv_direct(a, s);
 }
@@ -82,6 +83,8 @@ struct Step {
   int emit_stats = 0;      // CONV: its epilogue also writes the GroupNorm moments of its output
   int from_producer = 0;   // STATS: only merge the moments the producing convolution left behind
   size_t w_off = 0, b_off = 0, gamma_off = 0, beta_off = 0;
+  int sc_src = BUF_NONE, sc_cin = 0;   // CONV 3x3: a 1x1 shortcut over this buffer is folded into the contraction
+  size_t sc_w_off = 0, sc_b_off = 0;
   double flops = 0.0, bytes = 0.0;   // algorithmic work / HBM traffic of this step for one frame
   double flops_dense = 0.0;          // the same with an upsampling convolution priced as nine taps per output
 };
@@ -176,10 +179,15 @@ struct Builder {
     // a phase-decomposed upsampling convolution executes a 2x2 convolution per output: 4/9 of the products.
     // Only executed work is counted, never the work avoided.
     s.flops = conv_mfma_uses_phase(step_shape_args(d, s, 1)) ? s.flops_dense * 4.0 / 9.0 : s.flops_dense;
+    if (s.sc_src != BUF_NONE) {   // folded 1x1 shortcut: its products, its input and its weights
+      const double f = 2.0 * (double)s.sc_cin * s.cout * px_out;
+      s.flops += f; s.flops_dense += f;
+    }
     s.bytes = px_in * s.cin * (s.src == BUF_LATENT ? (double)dtype_size(d.cfg.latent_dtype) : es)                  // input, once
               + px_out * s.cout * (s.dst == BUF_OUT ? 4.0 : es)                 // output, once
               + (s.res != BUF_NONE ? px_out * s.cout * es : 0.0)                // residual, once
-              + (double)s.ksize * s.ksize * s.cin * s.cout * es;                // weights, once
+              + (double)s.ksize * s.ksize * s.cin * s.cout * es                 // weights, once
+              + (s.sc_src != BUF_NONE ? (px_out * s.sc_cin + (double)s.sc_cin * s.cout) * es : 0.0);   // shortcut input and weights
     d.flops += s.flops;
     d.flops_dense += s.flops_dense;
     d.launches += 1;
@@ -199,16 +207,23 @@ struct Builder {
     norm_params(name + ".norm2", cout, &c2.gamma_off, &c2.beta_off);
     conv_params(name + ".conv2", cout, cout, 3, &c2.w_off, &c2.b_off);
     Step sc; sc.kind = Step::CONV;
+    bool fold = false;
     if (cin != cout) {
       sc.src = a; sc.dst = c; sc.h = h; sc.w = w; sc.cin = cin; sc.cout = cout; sc.ksize = 1;
       conv_params(name + ".shortcut", cout, cin, 1, &sc.w_off, &sc.b_off);
-      c2.res = c;   // conv2 adds the shortcut it finds in its own output buffer
+      // The 1x1 shortcut becomes extra contraction steps of conv2 (K = 9*cout + cin) where the matrix-core kernel
+      // takes the layer; otherwise it stays a launch of its own that conv2 adds from its own output buffer.
+      ConvArgs probe = step_shape_args(d, c2, 1);
+      probe.res = nullptr;
+      fold = !d.cfg.separate_shortcut && conv_mfma_supported(probe) && cin % 32 == 0;
+      if (fold) { c2.sc_src = a; c2.sc_cin = cin; c2.sc_w_off = sc.w_off; c2.sc_b_off = sc.b_off; c2.res = BUF_NONE; }
+      else c2.res = c;   // conv2 adds the shortcut it finds in its own output buffer
     } else {
       c2.res = a;
     }
     stats(a, h, w, cin);
     d.steps.push_back(c1); count_conv(c1);
-    if (cin != cout) { d.steps.push_back(sc); count_conv(sc); }
+    if (cin != cout && !fold) { d.steps.push_back(sc); count_conv(sc); }
     stats(b, h, w, cout);
     d.steps.push_back(c2); count_conv(c2);
     track(h, w, cin); track(h, w, cout);
@@ -460,6 +475,36 @@ int wmdec_gn_silu_conv3x3(const void* x, int act_dtype, const float* mean, const
                     residual, y, y_dtype, n, h, w, cin, cout, stream);
 }
 
+int wmdec_gn_silu_conv3x3_shortcut(const void* x, int act_dtype, const float* mean, const float* rstd, const float* gamma,
+                                   const float* beta, int groups, int apply_silu, const void* w_packed, const float* bias,
+                                   const void* x2, int cin2, const void* w2_packed, const float* bias2, void* y, int y_dtype,
+                                   int n, int h, int w, int cin, int cout, void* stream) {
+  const char* who = "gn_silu_conv3x3_shortcut";
+  const int rc = check_conv(who, x, act_dtype, mean, rstd, gamma, beta, groups, w_packed, nullptr, y, y_dtype, n, h, w, cin, cout);
+  if (rc != WMDEC_OK) return rc;
+  WMDEC_REQUIRE(x2 && w2_packed && cin2 > 0, WMDEC_ERR_INVALID_ARG, "%s: null shortcut input or weights, or cin2 <= 0", who);
+  WMDEC_REQUIRE(aligned16(x2) && aligned16(w2_packed), WMDEC_ERR_INVALID_ARG, "%s: pointers must be 16-byte aligned", who);
+  WMDEC_REQUIRE(x2 != y, WMDEC_ERR_INVALID_ARG, "%s: x2 and y must not overlap", who);
+  ConvArgs a;
+  a.x = x; a.x_dtype = act_dtype; a.mean = mean; a.rstd = mean ? rstd : nullptr; a.gamma = gamma; a.beta = beta;
+  a.groups = mean ? groups : 1; a.silu = (mean && apply_silu) ? 1 : 0;
+  a.wt = w_packed; a.op_dtype = act_dtype; a.bias = bias; a.res_dtype = act_dtype;
+  a.y = y; a.y_dtype = y_dtype; a.n = n; a.h = h; a.w = w; a.cin = cin; a.cout = cout; a.ksize = 3;
+  if (conv_mfma_supported(a) && cin2 % 32 == 0) {   // one launch: the shortcut is part of the contraction
+    a.x2 = x2; a.cin2 = cin2; a.w2 = w2_packed; a.bias2 = bias2;
+    return launch_conv(a, (hipStream_t)stream);
+  }
+  // other shapes and fp32: the shortcut is written to y first, and the convolution adds it from there (every
+  // element is read and then written by the same thread)
+  ConvArgs sc;
+  sc.x = x2; sc.x_dtype = act_dtype; sc.wt = w2_packed; sc.op_dtype = act_dtype; sc.bias = bias2; sc.res_dtype = act_dtype;
+  sc.y = y; sc.y_dtype = y_dtype; sc.n = n; sc.h = h; sc.w = w; sc.cin = cin2; sc.cout = cout; sc.ksize = 1;
+  const int r1 = launch_conv_direct(sc, (hipStream_t)stream);
+  if (r1 != WMDEC_OK) return r1;
+  a.res = y; a.res_dtype = y_dtype;
+  return launch_conv_direct(a, (hipStream_t)stream);
+}
+
 // shape-only arguments of a 3x3 launch that also emits the moments of its output
 static ConvArgs stats_conv_shape(int act_dtype, int y_dtype, int n, int h, int w, int cin, int cout, int out_groups) {
   ConvArgs a;
@@ -619,7 +664,7 @@ void decoder_default_config(wmdec_decoder_config* cfg) {
   cfg->resblocks_per_level = 3;
   cfg->groups = 32; cfg->eps = 1e-6f; cfg->out_c = 3;
   cfg->act_dtype = WMDEC_F16; cfg->max_batch = 4;
-  cfg->latent_dtype = WMDEC_BF16; cfg->separate_stats_pass = 0;
+  cfg->latent_dtype = WMDEC_BF16; cfg->separate_stats_pass = 0; cfg->separate_shortcut = 0;
 }
 
 int decoder_create(const wmdec_decoder_config* cfg, wmdec_decoder** out) {
@@ -759,6 +804,7 @@ static int launch_step(wmdec_decoder* dec, const WsLayout& L, const Step& st, co
         a.wt = pk + st.w_off; a.bias = (const float*)(pk + st.b_off);
         if (st.upsample) a.wt_phase = pk + st.w_off + upconv_phase_offset_bytes(st.cout, st.cin, c.act_dtype);
         a.res = buf(st.res);
+        if (st.sc_src != BUF_NONE) { a.x2 = buf(st.sc_src); a.cin2 = st.sc_cin; a.w2 = pk + st.sc_w_off; a.bias2 = (const float*)(pk + st.sc_b_off); }
         if (st.dst == BUF_OUT) { a.y = out; a.y_dtype = WMDEC_F32; a.y_nchw = 1; }
         else if (st.to_attn == 1) { a.y = ws + L.qkv; a.y_dtype = c.act_dtype; }
         else { a.y = buf(st.dst); a.y_dtype = c.act_dtype; }

@@ -91,6 +91,10 @@ struct ConvArgs {
   int cin = 0, cout = 0;
   int ksize = 3;                 // 1 or 3
   int upsample = 0;              // 1: input is [n,h/2,w/2,cin], gathered at (y>>1, x>>1)
+  const void* x2 = nullptr;      // matrix-core 3x3 kernel only: y += W2 * x2 + bias2, the 1x1 shortcut of a channel-changing
+  const void* w2 = nullptr;      //   ResBlock folded into the contraction; x2 [n,h,w,cin2] of op_dtype, w2 packed with k = 1
+  const float* bias2 = nullptr;
+  int cin2 = 0;
   void* stats_ws = nullptr;      // non-null: also emit GroupNorm moments of y, [n][stats_groups][slots] triples
   int stats_groups = 0;
 };

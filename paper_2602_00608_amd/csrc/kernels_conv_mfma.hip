@@ -44,6 +44,9 @@ struct MfmaParams {
   int y_nchw;                    // 1: y is planar [n][cout][h][w] (the frame), else NHWC
   Moments* stats;                // non-null: moments of y per (sample, group, slot); slot = spatial tile * WM + wave row
   int stats_cpg, stats_groups, stats_slots;
+  // 1x1 shortcut folded into the contraction (3x3 only): y += W2 * x2 + bias2, x2 [n,h,w,cin2] taken as stored
+  const void* x2; const void* w2; const float* bias2;
+  int cin2, w2_bytes;
 };
 
 template <typename T> __device__ __forceinline__ void unpack8(const u32x4& v, float* f) {
@@ -65,7 +68,7 @@ constexpr int patch_floats(int ni) { return 32 * (ni * 32 + 4) > 2048 ? 32 * (ni
 
 template <typename T, typename TO, int MI, int NI, int MTW, int MTH, int MT_PER_ROW, bool RES>
 __device__ __forceinline__ void epilogue_store(const f32x16 (&acc)[MI][NI], float* lds, int lane, int mt0, int ty0,
-                                               int tx0, int co_w, const float* bias, const T* rin, TO* yout, int h,
+                                               int tx0, int co_w, const float* bias, const float* bias2, const T* rin, TO* yout, int h,
                                                int w_out, int cout, bool nchw, Moments* stats, int cpg, int stats_stride,
                                                int osc = 1, int oy_off = 0, int ox_off = 0) {
   // tile pixel (ty, tx) is output pixel (ty * osc + oy_off, tx * osc + ox_off): osc = 2 when the tile lives on the
@@ -85,7 +88,7 @@ __device__ __forceinline__ void epilogue_store(const f32x16 (&acc)[MI][NI], floa
         for (int r = 0; r < 16; ++r) lds[(8 * (r / 4) + 4 * lk + (r % 4)) * RW + ni * 32 + lm] = acc[mi][ni][r];
       if (oy < h && ox < w_out) {
         for (int c = lk; c < NI * 32 && co_w + c < cout; c += 2) {
-          const float v = lds[lm * RW + c] + (bias ? bias[co_w + c] : 0.f);
+          const float v = lds[lm * RW + c] + (bias ? bias[co_w + c] : 0.f) + (bias2 ? bias2[co_w + c] : 0.f);
           yout[((size_t)(co_w + c) * h + oy) * w_out + ox] = from_float<TO>(v);
         }
       }
@@ -98,7 +101,7 @@ __device__ __forceinline__ void epilogue_store(const f32x16 (&acc)[MI][NI], floa
   const int prow = lane / (NI * 4);     // first pixel row it reads; the others are prow + j * (64 / (NI*4))
   float bv[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) bv[e] = bias ? bias[co_w + cvec * 8 + e] : 0.f;
+  for (int e = 0; e < 8; ++e) bv[e] = (bias ? bias[co_w + cvec * 8 + e] : 0.f) + (bias2 ? bias2[co_w + cvec * 8 + e] : 0.f);
   // 32-bit element offset of this lane's vector in M tile mi, row j (or -1 outside the image)
   auto vec_off = [&](int mi, int j) -> int {
     const int mt = mt0 + mi;
@@ -407,6 +410,7 @@ void conv_mfma_kernel(MfmaParams p) {
   // has no halo: what its out-of-image pixels hold only reaches outputs that are never stored.
   int src_off[NV];          // byte offset of the vector in x (chunk 0)
   int dst_off[NV];          // element offset of its slot in a staged tile
+  int src_pix[NV];          // index of its source pixel in the sample (0 outside the image); only the shortcut phase reads it
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     const int v = tid + i * NT;
@@ -416,9 +420,11 @@ void conv_mfma_kernel(MfmaParams p) {
     const bool in_patch = v < HP * VPP;
     const bool inside = in_patch && gy >= 0 && gy < h_t && gx >= 0 && gx < w_t;
     src_off[i] = 0;
+    src_pix[i] = 0;
     if (inside) {
       const int sy = (!PH && p.upsample) ? gy >> 1 : gy, sx = (!PH && p.upsample) ? gx >> 1 : gx;
-      src_off[i] = ((sy * w_in + sx) * p.cin + cvec * 8) * (int)sizeof(T);
+      src_pix[i] = sy * w_in + sx;
+      src_off[i] = (src_pix[i] * p.cin + cvec * 8) * (int)sizeof(T);
     }
     const bool keep = KS == 1 ? in_patch : inside;
     dst_off[i] = (keep ? hy * ROW + hx * PS : SPARE) + cvec * 8;
@@ -473,6 +479,50 @@ void conv_mfma_kernel(MfmaParams p) {
   constexpr int SPREAD_AVG = (NV * 8 * (ACT == 2 ? 8 : 3) + (SLOTS - SLOTS / 3) * NI - 1) / ((SLOTS - SLOTS / 3) * NI);
   constexpr int SPREAD = (ACT == 0 || MI * NI > 4) ? -1 : (SPREAD_AVG > 1 ? SPREAD_AVG - 1 : 1);
   f32x4 abv[2];   // table entries of the part being activated and of the next one (sliced activation)
+
+  // ---- shortcut phase (3x3 kernels with a second input): acc = W2 * x2 over the tile's own pixels, a 1x1
+  // contraction over cin2 channels taken as stored (no normalisation).  Chunks of KC channels go through the same
+  // two LDS buffers with the tile's halo layout (only the centre tap is read), loads two chunks ahead; the main
+  // loop below then adds the 3x3 contraction to the same accumulators, so the shortcut tensor never exists in
+  // memory and the epilogue adds both biases.
+  if constexpr (KS == 3 && !PH) {
+    if (p.x2) {
+      const char* xin2 = reinterpret_cast<const char*>(p.x2) + (size_t)n * p.h * p.w_out * p.cin2 * sizeof(T);
+      const int nch2 = p.cin2 / KC;
+      auto issue2 = [&](int chunk) {
+        const int cb = min(chunk, nch2 - 1) * KC * (int)sizeof(T);
+#pragma unroll
+        for (int i = 0; i < NV; ++i)
+          raw[i] = *reinterpret_cast<const u32x4*>(xin2 + (unsigned)((src_pix[i] * p.cin2 + cvec * 8) * (int)sizeof(T) + cb));
+      };
+      auto store_all = [&](T* buf) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) store_vec(i, buf);
+      };
+      int a_ctr[MI];   // centre tap of the halo patch
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi) a_ctr[mi] = a_off[mi] + PAD * ROW + PAD * PS;
+      constexpr int D2 = 2;
+      const __amdgpu_buffer_rsrc_t wrsrc2 = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p.w2), 0, p.w2_bytes, 0x00020000);
+      const int wcol2 = ((co0 >> 5) + wn * NI) * 1024;
+      u32x4 bq2[D2][NI];
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni) bq2[0][ni] = load_fragment(wrsrc2, lane16, wcol2 + ni * 1024);
+      issue2(0);
+      store_all(s_a);
+      issue2(1);
+      __syncthreads();
+      auto none = [](auto) {};
+      for (int c = 0; c < nch2; ++c) {
+        const int bcur = wcol2 + c * KK * kk_stride;
+        const int bnext = c + 1 < nch2 ? bcur + KK * kk_stride : bcur;
+        mfma_chunk<T, MI, NI, 1, KC, ROW, PS, D2, false, -1>(s_a + (c & 1) * BUF, a_ctr, wrsrc2, bcur, bnext, 0, kk_stride, lane16, bq2, acc, none);
+        if (c + 1 < nch2) store_all(s_a + ((c + 1) & 1) * BUF);
+        issue2(c + 2);
+        __syncthreads();
+      }
+    }
+  }
 
   issue(0);
   // (built behind the first chunk's loads, so that its own global loads overlap them)
@@ -539,11 +589,11 @@ void conv_mfma_kernel(MfmaParams p) {
   Moments* st = p.stats ? p.stats + (size_t)n * p.stats_groups * p.stats_slots + (tile * WM + wm) : nullptr;
   if (rin)
     epilogue_store<T, TO, MI, NI, MTW, MTH, MT_PER_ROW, true>(acc, patch, lane, PH ? 0 : wm * MI, ty0, tx0, co0 + wn * NI * 32, p.bias,
-                                                              rin, yout, p.h, p.w_out, p.cout, false, st, p.stats_cpg, p.stats_slots,
+                                                              p.bias2, rin, yout, p.h, p.w_out, p.cout, false, st, p.stats_cpg, p.stats_slots,
                                                               PH ? 2 : 1, PH ? wave >> 1 : 0, PH ? wave & 1 : 0);
   else
     epilogue_store<T, TO, MI, NI, MTW, MTH, MT_PER_ROW, false>(acc, patch, lane, PH ? 0 : wm * MI, ty0, tx0, co0 + wn * NI * 32, p.bias,
-                                                               rin, yout, p.h, p.w_out, p.cout, p.y_nchw != 0, st, p.stats_cpg, p.stats_slots,
+                                                               p.bias2, rin, yout, p.h, p.w_out, p.cout, p.y_nchw != 0, st, p.stats_cpg, p.stats_slots,
                                                                PH ? 2 : 1, PH ? wave >> 1 : 0, PH ? wave & 1 : 0);
 }
 
@@ -564,6 +614,13 @@ int launch_cfg(const ConvArgs& a, hipStream_t s) {
   p.w_bytes = (int)(packed_elems(PH ? 16 : KS * KS, a.cout, a.cin) * sizeof(T));
   p.stats = (Moments*)a.stats_ws; p.stats_groups = a.stats_groups; p.stats_cpg = a.stats_groups > 0 ? a.cout / a.stats_groups : 1;
   p.stats_slots = p.tiles_x * p.tiles_y * WM;
+  p.x2 = nullptr; p.w2 = nullptr; p.bias2 = nullptr; p.cin2 = 0; p.w2_bytes = 0;
+  if (a.x2) {
+    WMDEC_REQUIRE(KS == 3 && !PH && a.w2 && a.cin2 > 0 && a.cin2 % KC == 0 && (long)a.h * a.w * a.cin2 < (1L << 29), WMDEC_ERR_UNSUPPORTED,
+                  "conv_mfma: a folded shortcut needs a 3x3 convolution without upsampling and cin2 %% %d == 0", KC);
+    p.x2 = a.x2; p.w2 = a.w2; p.bias2 = a.bias2; p.cin2 = a.cin2;
+    p.w2_bytes = (int)(packed_elems(1, a.cout, a.cin2) * sizeof(T));
+  }
   constexpr int NT = 64 * WM * WN;
   size_t smem = (((size_t)2 * tile_buf_elems(TH, TW, PAD, KC) * 2 + 15) & ~(size_t)15) + (size_t)a.cin * sizeof(float2);
   const size_t patch = (size_t)(WM * WN) * patch_floats(NI) * sizeof(float);   // epilogue patches of the wavefronts

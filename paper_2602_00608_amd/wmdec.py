@@ -29,7 +29,8 @@ class DecoderConfig(ctypes.Structure):
                 ("num_levels", ctypes.c_int), ("level_channels", ctypes.c_int * 4),
                 ("resblocks_per_level", ctypes.c_int), ("groups", ctypes.c_int), ("eps", ctypes.c_float),
                 ("out_c", ctypes.c_int), ("act_dtype", ctypes.c_int), ("max_batch", ctypes.c_int),
-                ("latent_dtype", ctypes.c_int), ("separate_stats_pass", ctypes.c_int)]
+                ("latent_dtype", ctypes.c_int), ("separate_stats_pass", ctypes.c_int),
+                ("separate_shortcut", ctypes.c_int)]
 
 
 _vp, _i, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
@@ -44,6 +45,8 @@ SIGNATURES = {
     "wmdec_conv_packed_bytes": (_sz, [_i] * 4),
     "wmdec_pack_conv_weights": (_i, [_vp, _i, _i, _i, _i, _vp, _i, _vp]),
     "wmdec_gn_silu_conv3x3": (_i, [_vp, _i, _vp, _vp, _vp, _vp, _i, _i, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp]),
+    "wmdec_gn_silu_conv3x3_shortcut": (_i, [_vp, _i, _vp, _vp, _vp, _vp, _i, _i, _vp, _vp, _vp, _i, _vp, _vp, _vp, _i,
+                                            _i, _i, _i, _i, _i, _vp]),
     "wmdec_conv_stats_workspace_bytes": (_sz, [_i] * 8),
     "wmdec_gn_silu_conv3x3_stats": (_i, [_vp, _i, _vp, _vp, _vp, _vp, _i, _i, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i,
                                          _i, _f, _vp, _vp, _vp, _sz, _vp]),
@@ -162,6 +165,15 @@ def _conv(fn, x, mean, rstd, gamma, beta, groups, apply_silu, w_packed, bias, re
 def gn_silu_conv3x3(x, mean, rstd, gamma, beta, groups, apply_silu, w_packed, bias, residual, y):
     _conv(lib().wmdec_gn_silu_conv3x3, x, mean, rstd, gamma, beta, groups, apply_silu, w_packed, bias, residual, y,
           x.shape[3], y.shape[3])
+
+
+def gn_silu_conv3x3_shortcut(x, mean, rstd, gamma, beta, groups, apply_silu, w_packed, bias, x2, w2_packed, bias2, y):
+    """y = conv3x3(act(x)) + bias + W2 * x2 + bias2 (the 1x1 shortcut of a channel-changing ResBlock folded in)."""
+    n, h, w, _ = y.shape
+    _check(lib().wmdec_gn_silu_conv3x3_shortcut(
+        _ptr(x), dtype_enum(x), _ptr(mean), _ptr(rstd), _ptr(gamma), _ptr(beta), groups, int(apply_silu), _ptr(w_packed),
+        _ptr(bias), _ptr(x2), x2.shape[3], _ptr(w2_packed), _ptr(bias2), _ptr(y), dtype_enum(y), n, h, w, x.shape[3],
+        y.shape[3], _stream()))
 
 
 def conv_stats_workspace_bytes(act_dtype, y_dtype, n, h, w, cin, cout, out_groups):

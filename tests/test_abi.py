@@ -96,7 +96,13 @@ def test_step_accounting_adds_up():
     assert abs(sum(f for _, f, _ in info) - dec.flops_per_frame()) / dec.flops_per_frame() < 1e-12
     assert all(k for k, _, _ in info)
     convs = [(k, f, b) for k, f, b in info if k.startswith("conv_mfma_kernel<")]
-    assert len(convs) >= 36 and all(k.endswith(">") for k, _, _ in convs)
+    # 30 ResBlock convolutions (the two 1x1 shortcuts are folded into their second convolutions), three upsampling
+    # convolutions, qkv and output projection, conv_out: 36 - 2 launches on the matrix cores
+    assert len(convs) == 34 and all(k.endswith(">") for k, _, _ in convs)
+    # the second convolution of the 512 -> 256 block carries its shortcut: K = 9*256 + 512, and reads the block input
+    fold_flops = 2.0 * (9 * 256 + 512) * 256 * 240 * 360
+    fold_bytes = (2 * 240 * 360 * 256 + 240 * 360 * 512) * 2 + (9 * 256 * 256 + 512 * 256) * 2
+    assert any(f == fold_flops and b == fold_bytes for _, f, b in convs)
     # last ResBlock convolution at 480x720: 128 -> 128, f16, with residual
     want_flops = 2.0 * 9 * 128 * 128 * 480 * 720
     want_bytes = 3 * 480 * 720 * 128 * 2 + 9 * 128 * 128 * 2
@@ -143,6 +149,13 @@ def test_argument_errors_are_reported_without_a_gpu():
                                          32, 1e-6, p, p, p, 16, None) == wmdec.ERR_WORKSPACE
     assert l.wmdec_gn_silu_conv3x3_stats(p, 0, None, None, None, None, 32, 0, p, None, None, 2 * p, 0, 1, 8, 8, 64, 64,
                                          32, 1e-6, p, p, p, 1 << 20, None) == wmdec.ERR_UNSUPPORTED
+    # convolution with the folded shortcut
+    assert l.wmdec_gn_silu_conv3x3_shortcut(p, 2, None, None, None, None, 32, 0, p, None, None, 64, p, None, 2 * p, 2,
+                                            1, 8, 8, 64, 64, None) == wmdec.ERR_INVALID_ARG       # no x2
+    assert l.wmdec_gn_silu_conv3x3_shortcut(p, 2, None, None, None, None, 32, 0, p, None, 3 * p, 0, p, None, 2 * p, 2,
+                                            1, 8, 8, 64, 64, None) == wmdec.ERR_INVALID_ARG       # cin2 = 0
+    assert l.wmdec_gn_silu_conv3x3_shortcut(p, 2, None, None, None, None, 32, 0, p, None, 2 * p, 64, p, None, 2 * p, 2,
+                                            1, 8, 8, 64, 64, None) == wmdec.ERR_INVALID_ARG       # x2 == y
     # latent extrapolation
     assert l.wmdec_latent_extrapolate(p, None, 1, 0.5, 1, p, 1, 16, None) == wmdec.ERR_INVALID_ARG
     assert l.wmdec_latent_extrapolate(p, p, 1, float("nan"), 1, p, 1, 16, None) == wmdec.ERR_INVALID_ARG

@@ -408,6 +408,50 @@ def test_statistics_from_the_epilogue_match_the_statistics_pass():
     assert ref.rel_err(outs[0], outs[1]) <= G.TOL["f16"], ref.rel_err(outs[0], outs[1])
 
 
+def test_folded_shortcut_against_separate_shortcut_and_the_oracle():
+    """The 1x1 shortcut of the channel-changing ResBlocks as extra contraction steps of the second convolution
+    (default) and as a launch of its own: both graphs against the oracle; fewer launches with the fold."""
+    chans = (512, 128, 64, 64)
+    spec = synth.decoder_weight_spec(level_channels=chans, resblocks_per_level=2)
+    weights = synth.draw_params(spec, synth.weight_seed(11), random_affine=True)
+    z = synth.latent_sequence(workload=11, frames=2, h=9, w=11)
+    want = ref.decoder(z, weights, level_channels=chans, resblocks_per_level=2, groups=32, eps=1e-6)
+    launches = []
+    for separate in (0, 1):
+        cfg = small_cfg(wmdec.F16)
+        cfg.latent_h, cfg.latent_w = 9, 11
+        cfg.level_channels[3] = 64
+        cfg.separate_shortcut = separate
+        dec = wmdec.Decoder(cfg)
+        launches.append(dec.num_launches())
+        dec.close()
+        got = run_decoder(cfg, weights, z)
+        assert ref.rel_err(got, want) <= G.TOL["f16"], separate
+    assert launches[1] - launches[0] == 2        # two channel-changing blocks: 512 -> 128 and 128 -> 64
+
+
+def test_channel_changing_resblock_full_size_with_folded_shortcut():
+    """The decoder's first 240x360 ResBlock at its stated size, 512 -> 256 channels, through the per-op entry points
+    with the shortcut folded into the second convolution, against the oracle's ResBlock."""
+    dtype, groups, eps = "f16", 32, 1e-6
+    x = synth.activation(6, (1, 512, 240, 360), True)
+    p = resblock_params(synth.weight_seed(6), 512, 256, True)
+    xd = G.dev_nhwc(x, dtype)
+    m1, r1 = G.gn_stats(xd, groups, eps)
+    hbuf = torch.empty((1, 240, 360, 256), dtype=G.TORCH[dtype], device="cuda")
+    wmdec.gn_silu_conv3x3(xd, m1, r1, G.dev_f32(p["norm1.gamma"]), G.dev_f32(p["norm1.beta"]), groups, True,
+                          G.pack(p["conv1.w"], dtype), G.dev_f32(p["conv1.b"]), None, hbuf)
+    m2, r2 = G.gn_stats(hbuf, groups, eps)
+    y = torch.empty((1, 240, 360, 256), dtype=torch.float32, device="cuda")
+    wmdec.gn_silu_conv3x3_shortcut(hbuf, m2, r2, G.dev_f32(p["norm2.gamma"]), G.dev_f32(p["norm2.beta"]), groups, True,
+                                   G.pack(p["conv2.w"], dtype), G.dev_f32(p["conv2.b"]), xd, G.pack(p["shortcut.w"], dtype),
+                                   G.dev_f32(p["shortcut.b"]), y)
+    torch.cuda.synchronize()
+    err = ref.rel_err(G.host_nchw(y), ref.resblock(x, p, groups, eps))
+    print("512 -> 256 @240x360 ResBlock, folded shortcut: max|err|/rms = %.3e" % err)
+    assert err <= G.TOL[dtype], err
+
+
 # ------------------------------------------------------------------ latent extrapolation in front of the decoder
 def test_extrapolated_run_equals_decode_of_the_explicit_sum_bitwise():
     """decoder_run_extrapolated forms z + (j+1)*lambda*v while conv_in stages its input.  wmdec_latent_extrapolate

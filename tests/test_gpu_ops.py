@@ -260,6 +260,39 @@ def test_conv_epilogue_statistics_unsupported_shapes_are_refused():
     assert e.value.status == wmdec.ERR_UNSUPPORTED
 
 
+# second convolution of a channel-changing ResBlock with the 1x1 shortcut folded into its contraction
+@pytest.mark.parametrize("dtype,ydtype,n,cin,cin2,cout,h,w", [
+    ("f16", "f32", 1, 256, 512, 256, 24, 36),       # 128 x 128 tile, wavefronts 2x2
+    ("bf16", "bf16", 2, 128, 256, 128, 40, 56),
+    ("f16", "f16", 1, 64, 96, 64, 17, 33),          # 128 x 64 tile, ragged, cin2 not a multiple of 64
+    ("f16", "f16", 1, 32, 64, 32, 20, 28),          # cout % 64 != 0: two launches of the general kernel
+    ("f32", "f32", 1, 24, 12, 40, 7, 9),            # fp32 path
+    ("f16", "f16", 1, 256, 512, 256, 240, 360),     # full size: tile with one weight fragment per four MFMAs
+    ("f16", "f32", 1, 128, 256, 128, 480, 720),     # full size: 256 x 128 tile
+    ("bf16", "f32", 1, 128, 256, 128, 480, 720),
+])
+def test_gn_silu_conv3x3_shortcut(dtype, ydtype, n, cin, cin2, cout, h, w):
+    r = rng(15)
+    sixteen = dtype != "f32"
+    x = G.stored(r.standard_normal((n, cin, h, w)) * 1.3 + 0.2, dtype)
+    x2 = G.stored(r.standard_normal((n, cin2, h, w)), dtype)
+    wt, b = synth.conv_params(r, cout, cin, 3, sixteen)
+    w2, b2 = synth.conv_params(r, cout, cin2, 1, sixteen)
+    groups = 32 if cin % 32 == 0 else 4
+    gamma = (1 + 0.2 * r.standard_normal(cin)).astype(np.float32)
+    beta = (0.2 * r.standard_normal(cin)).astype(np.float32)
+    xd, x2d = G.dev_nhwc(x, dtype), G.dev_nhwc(x2, dtype)
+    mean, rstd = G.gn_stats(xd, groups, 1e-6)
+    y, check = G.canaried((n, h, w, cout), G.TORCH[ydtype])
+    wmdec.gn_silu_conv3x3_shortcut(xd, mean, rstd, G.dev_f32(gamma), G.dev_f32(beta), groups, True, G.pack(wt, dtype),
+                                   G.dev_f32(b), x2d, G.pack(w2, dtype), G.dev_f32(b2), y)
+    torch.cuda.synchronize()
+    check()
+    want = ref.conv2d(ref.group_norm(x, groups, 1e-6, gamma, beta, apply_silu=True), wt, b) + ref.conv2d(x2, w2, b2)
+    err = ref.rel_err(G.host_nchw(y), want)
+    assert err <= G.TOL[dtype] / (2 if sixteen and ydtype == "f32" else 1), err
+
+
 def test_conv_padding_is_applied_after_activation():
     # constant input, beta chosen so that SiLU(GN(x)) != 0: border outputs must see zeros, not SiLU(beta)
     x = np.full((1, 32, 6, 6), 3.0, np.float32)
