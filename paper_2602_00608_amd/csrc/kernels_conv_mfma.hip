@@ -642,17 +642,16 @@ int launch_cfg(const ConvArgs& a, hipStream_t s) {
 
 // Tile shapes: patch height x width, wavefront rows x columns, 32-channel tiles per wavefront.
 struct TileShape { int th, tw, wm, wn, ni; };
-enum TileId { T256x128 = 0, T128x128_ROW, T128x64_ROW, T128x128, T128x64, T256x32, T_PHASE, T128x128_1x4, kNumTiles };
+enum TileId { T256x128 = 0, T128x128_ROW, T128x64_ROW, T128x64, T256x32, T_PHASE, T128x128_1x4, kNumTiles };
 constexpr TileShape kTiles[kNumTiles] = {
-    {8, 32, 2, 2, 2},    // T256x128: 256 pixels x 128 channels
+    {8, 32, 2, 2, 2},    // T256x128: 256 pixels x 128 channels (large 1x1 convolutions)
     {4, 32, 2, 2, 2},    // T128x128_ROW: 128 x 128 on a 4x32 patch (1x1 convolutions)
     {4, 32, 4, 1, 2},    // T128x64_ROW: 128 x 64 on a 4x32 patch (1x1 convolutions)
-    {8, 16, 2, 2, 2},    // T128x128: 128 x 128 on an 8x16 patch, wavefronts 2x2
     {8, 16, 4, 1, 2},    // T128x64: 128 x 64 on an 8x16 patch
     {8, 32, 4, 1, 1},    // T256x32: 256 x 32 (few output channels: the frame)
     {8, 16, 4, 1, 2},    // T_PHASE: phase-decomposed upsampling convolution: 8x16 input pixels (16x32 outputs) x 64 channels
     {8, 16, 1, 4, 1},    // T128x128_1x4: 128 x 128, every wavefront all pixels x 32 channels: a weight fragment feeds four
-                         //     MFMAs (two in T128x128), which halves the load on the vector L1 (64 B/clk per compute unit)
+                         //     MFMAs, which keeps the fragment loads off the limit of the vector L1 (64 B/clk per compute unit)
 };
 
 // which tile shape a launch uses; a function of the per-sample shape only, so that the tiling, hence every summation
@@ -663,11 +662,10 @@ TileId pick_tile(const ConvArgs& a) {
   if (a.ksize == 3) {
     if (conv_mfma_uses_phase(a)) return T_PHASE;
     if (a.cout <= 32) return T256x32;
-    if (!n128) return T128x64;
-    // 256-pixel tiles when that still gives three per compute unit; else 128-pixel tiles, with one weight
-    // fragment per four MFMAs unless the layer leaves compute units empty anyway
-    const long work = px * (a.cout / 128);
-    return work >= 256L * 256 * 3 ? T256x128 : (work >= 128L * 256 * 2 ? T128x128_1x4 : T128x128);
+    // 128 pixels x 128 channels with every wavefront on all pixels x 32 channels (three workgroups per compute unit):
+    // measured against the 256-pixel tile and the 2x2 wavefront layout on every layer shape of the decoder, it is
+    // equal or faster everywhere (128 -> 128 at 480x720: 110 against 120 us; 512 -> 512 at 60x90: 33.5 against 35.1)
+    return n128 ? T128x128_1x4 : T128x64;
   }
   if (n128 && a.cin % 64 == 0 && px * (a.cout / 128) >= 256L * 256 * 2) return T256x128;
   return n128 ? T128x128_ROW : T128x64_ROW;
@@ -676,8 +674,6 @@ TileId pick_tile(const ConvArgs& a) {
 template <typename T, typename TO>
 int launch_3x3(const ConvArgs& a, hipStream_t s) {
   switch (pick_tile(a)) {
-    case T256x128: return launch_cfg<T, TO, 8, 32, 2, 2, 2, 3, 32>(a, s);
-    case T128x128: return launch_cfg<T, TO, 8, 16, 2, 2, 2, 3, 32>(a, s);
     case T128x64: return launch_cfg<T, TO, 8, 16, 4, 1, 2, 3, 32>(a, s);
     case T_PHASE: return launch_cfg<T, TO, 8, 16, 4, 1, 2, 3, 32, true>(a, s);
     case T128x128_1x4: return launch_cfg<T, TO, 8, 16, 1, 4, 1, 3, 32>(a, s);
