@@ -642,7 +642,7 @@ int launch_cfg(const ConvArgs& a, hipStream_t s) {
 
 // Tile shapes: patch height x width, wavefront rows x columns, 32-channel tiles per wavefront.
 struct TileShape { int th, tw, wm, wn, ni; };
-enum TileId { T256x128 = 0, T128x128_ROW, T128x64_ROW, T128x64, T256x32, T_PHASE, T128x128_1x4, kNumTiles };
+enum TileId { T256x128 = 0, T128x128_ROW, T128x64_ROW, T128x64, T256x32, T_PHASE, T128x128_1x4, T128x256, kNumTiles };
 constexpr TileShape kTiles[kNumTiles] = {
     {8, 32, 2, 2, 2},    // T256x128: 256 pixels x 128 channels (large 1x1 convolutions)
     {4, 32, 2, 2, 2},    // T128x128_ROW: 128 x 128 on a 4x32 patch (1x1 convolutions)
@@ -652,6 +652,9 @@ constexpr TileShape kTiles[kNumTiles] = {
     {8, 16, 4, 1, 2},    // T_PHASE: phase-decomposed upsampling convolution: 8x16 input pixels (16x32 outputs) x 64 channels
     {8, 16, 1, 4, 1},    // T128x128_1x4: 128 x 128, every wavefront all pixels x 32 channels: a weight fragment feeds four
                          //     MFMAs, which keeps the fragment loads off the limit of the vector L1 (64 B/clk per compute unit)
+    {8, 16, 1, 4, 2},    // T128x256: 128 x 256, every wavefront all pixels x 64 channels: a staged (normalised, activated) patch
+                         //     feeds twice the channels, i.e. half the staging work and input traffic per MFMA; two
+                         //     workgroups per compute unit
 };
 
 // which tile shape a launch uses; a function of the per-sample shape only, so that the tiling, hence every summation
@@ -665,6 +668,10 @@ TileId pick_tile(const ConvArgs& a) {
     // 128 pixels x 128 channels with every wavefront on all pixels x 32 channels (three workgroups per compute unit):
     // measured against the 256-pixel tile and the 2x2 wavefront layout on every layer shape of the decoder, it is
     // equal or faster everywhere (128 -> 128 at 480x720: 110 against 120 us; 512 -> 512 at 60x90: 33.5 against 35.1)
+    // With 256 channels per workgroup the normalise + SiLU work and the input traffic per MFMA halve, at two workgroups
+    // per compute unit instead of three: it pays (6 to 8 %) where that still leaves every compute unit two workgroups
+    // (the 240x360 layers of the decoder), and loses on smaller layers.
+    if (a.cout % 256 == 0 && ((px + 127) / 128) * (a.cout / 256) >= 2 * 256) return T128x256;
     return n128 ? T128x128_1x4 : T128x64;
   }
   if (n128 && a.cin % 64 == 0 && px * (a.cout / 128) >= 256L * 256 * 2) return T256x128;
@@ -677,6 +684,7 @@ int launch_3x3(const ConvArgs& a, hipStream_t s) {
     case T128x64: return launch_cfg<T, TO, 8, 16, 4, 1, 2, 3, 32>(a, s);
     case T_PHASE: return launch_cfg<T, TO, 8, 16, 4, 1, 2, 3, 32, true>(a, s);
     case T128x128_1x4: return launch_cfg<T, TO, 8, 16, 1, 4, 1, 3, 32>(a, s);
+    case T128x256: return launch_cfg<T, TO, 8, 16, 1, 4, 2, 3, 32>(a, s);
     default: return launch_cfg<T, TO, 8, 32, 4, 1, 1, 3, 32>(a, s);
   }
 }

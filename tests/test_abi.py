@@ -141,7 +141,7 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert l.wmdec_gn_stats_noalloc(p, 1, 65, 2, 2, 32, 32, 1e-6, p, p, None) == wmdec.ERR_WORKSPACE
     assert b"limit" in l.wmdec_last_error()
     # convolution that also emits the moments of its output
-    assert l.wmdec_conv_stats_workspace_bytes(wmdec.F16, wmdec.F16, 1, 480, 720, 128, 128, 32) == 32 * 60 * 23 * 2 * 12
+    assert l.wmdec_conv_stats_workspace_bytes(wmdec.F16, wmdec.F16, 1, 480, 720, 128, 128, 32) == 32 * 60 * 45 * 12   # one triple per group and 8x16 tile
     assert l.wmdec_conv_stats_workspace_bytes(wmdec.F32, wmdec.F32, 1, 8, 8, 64, 64, 32) == 0
     assert l.wmdec_gn_silu_conv3x3_stats(p, 2, None, None, None, None, 32, 0, p, None, None, 2 * p, 2, 1, 8, 8, 64, 64,
                                          24, 1e-6, p, p, p, 1 << 20, None) == wmdec.ERR_SHAPE
