@@ -46,6 +46,9 @@ def main():
     ap.add_argument("--separate-stats", action="store_true",
                     help="ablation: every GroupNorm runs the streaming statistics pass instead of taking the moments from "
                          "the producing convolution's epilogue")
+    ap.add_argument("--separate-merge", action="store_true",
+                    help="ablation: a small launch merges the moments a convolution emitted, instead of the hand-over "
+                         "inside producer and consumer")
     ap.add_argument("--separate-shortcut", action="store_true",
                     help="ablation: the 1x1 shortcuts are launches of their own instead of contraction steps of conv2")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -77,6 +80,7 @@ def main():
     cfg.max_batch = max(4, args.batch)
     cfg.separate_stats_pass = int(args.separate_stats)
     cfg.separate_shortcut = int(args.separate_shortcut)
+    cfg.separate_merge_launch = int(args.separate_merge)
     dec = wmdec.Decoder(cfg)
     weights = synth.decoder_weights(4)
     blob = np.zeros(dec.weights_bytes(), np.uint8)
@@ -174,7 +178,8 @@ def main():
                    "gflop_per_frame": round(dec.flops_per_frame() / 1e9, 1),
                    "gflop_per_frame_if_upsampling_convs_ran_nine_taps": round(dec.dense_flops_per_frame() / 1e9, 1),
                    "launches_per_step": dec.num_launches(),
-                   "graph": {"statistics": "separate pass" if args.separate_stats else "from the producer's epilogue",
+                   "graph": {"statistics": "separate pass" if args.separate_stats else ("from the producer's epilogue, merged by a launch"
+                                            if args.separate_merge else "from the producer's epilogue, no merge launch"),
                              "shortcut": "separate launch" if args.separate_shortcut else "folded into conv2"}},
         "tflops": round(dec.flops_per_frame() * fps / 1e12, 1),
         "roofline": roofline, "cpu_baseline": cpu, "kernel_families": families}))

@@ -254,13 +254,18 @@ typedef struct {
   int separate_stats_pass;          /* 0: a GroupNorm takes its statistics from the epilogue of the convolution that
                                        produced its input (no extra read of the tensor); 1: every GroupNorm runs the
                                        streaming statistics pass (wmdec_gn_stats) -- the graph before that fusion */
+  int separate_merge_launch;        /* 0: where producer and consumer of a GroupNorm's statistics are both matrix-core
+                                       convolutions, the producer's last workgroup per tile row merges that row's partial
+                                       moments and the consumer merges the rows in its prologue: no launch in between;
+                                       1: a small merge launch (the graph before that fusion) */
   int separate_shortcut;            /* 0: the 1x1 shortcut of a channel-changing ResBlock is folded into the contraction
                                        of the block's second convolution; 1: it is a launch of its own whose output the
                                        second convolution adds -- the graph before that fusion */
 } wmdec_decoder_config;
 
 /* Fills *cfg with the 720x480 decoder above (act_dtype = WMDEC_F16, max_batch = 4,
- * latent_dtype = WMDEC_BF16, separate_stats_pass = 0, separate_shortcut = 0). */
+ * latent_dtype = WMDEC_BF16, separate_stats_pass = 0, separate_merge_launch = 0,
+ * separate_shortcut = 0). */
 void decoder_default_config(wmdec_decoder_config* cfg);
 
 /* Validates cfg and builds the host-side plan.  Allocates no device memory. */

@@ -75,13 +75,16 @@ struct Param {  // one canonical parameter
 };
 
 struct Step {
-  enum Kind { STATS, CONV, QKV_TRANSPOSE_V, FLASH } kind;
+  enum Kind { STATS, CONV, QKV_TRANSPOSE_V, FLASH, NONE } kind;
   int src = BUF_NONE, dst = BUF_NONE, res = BUF_NONE;
   int h = 0, w = 0, cin = 0, cout = 0;   // conv: OUTPUT h, w; stats: tensor h, w, c = cin
   int ksize = 3, upsample = 0, norm = 0, silu = 0;
   int x_nchw = 0, y_nchw = 0, to_attn = 0 /*1: dst is the qkv buffer, 2: src is the attention output*/;
   int emit_stats = 0;      // CONV: its epilogue also writes the GroupNorm moments of its output
   int from_producer = 0;   // STATS: only merge the moments the producing convolution left behind
+  int emit_rows = -1;      // CONV (with emit_stats): also leaves row moments in row buffer 0 / 1; no merge launch follows
+  int rows_from = -1;      // CONV with norm: takes the statistics of its input from row buffer 0 / 1 ...
+  int rows_count = 0;      //   ... which holds this many rows per (sample, group)
   size_t w_off = 0, b_off = 0, gamma_off = 0, beta_off = 0;
   int sc_src = BUF_NONE, sc_cin = 0;   // CONV 3x3: a 1x1 shortcut over this buffer is folded into the contraction
   size_t sc_w_off = 0, sc_b_off = 0;
@@ -235,6 +238,7 @@ struct Builder {
 // a merge of those moments: the tensor is not read again.  One partial buffer exists, so a producer is used
 // only if no other emitting convolution runs between it and its statistics step.
 static void fuse_stats_into_producers(wmdec_decoder& d) {
+  int parity = 0;
   for (size_t i = 0; i < d.steps.size(); ++i) {
     Step& st = d.steps[i];
     if (st.kind != Step::STATS || st.src < 0) continue;
@@ -248,7 +252,30 @@ static void fuse_stats_into_producers(wmdec_decoder& d) {
     st.from_producer = 1;
     st.bytes = 0.0;          // no tensor traffic left in this step
     d.launches -= gn_stats_num_launches(d.cfg.act_dtype, st.h, st.w, st.cin, d.cfg.groups) - 1;   // one merge launch remains
+    // The consumer of these statistics is the next step.  If it is a matrix-core convolution, the producer's last
+    // workgroup per tile row merges that row and the consumer merges the rows while it builds its scale/shift table:
+    // the merge launch disappears.  Two row buffers alternate, because a consumer is usually the next producer.
+    if (d.cfg.separate_merge_launch || i + 1 >= d.steps.size()) continue;
+    Step& cons = d.steps[i + 1];
+    if (cons.kind != Step::CONV || !cons.norm || cons.src != st.src || !conv_mfma_supported(step_shape_args(d, cons, 1))) continue;
+    int rows = 0, ctiles = 0, per_row = 0;
+    conv_mfma_row_extents(step_shape_args(d, d.steps[j], 1), &rows, &ctiles, &per_row);
+    if (rows > 64) continue;   // the consumer's prologue merges at most 64 rows
+    // The hand-over keeps every workgroup of the producer resident for two more memory round trips (its stores, its
+    // ticket).  Measured, that costs a launch of several rounds of workgroups as much as the merge launch it saves;
+    // it wins where the producer is a single round (at most three workgroups per compute unit, per sample).
+    if ((long)rows * per_row * ctiles > 3 * 256) continue;
+    d.steps[j].emit_rows = parity;
+    cons.rows_from = parity;
+    cons.rows_count = rows;
+    parity ^= 1;
+    st.kind = Step::NONE;    // removed below
+    d.launches -= 1;
   }
+  std::vector<Step> kept;
+  for (const Step& st : d.steps)
+    if (st.kind != Step::NONE) kept.push_back(st);
+  d.steps.swap(kept);
 }
 
 static int build_plan(wmdec_decoder& d) {
@@ -343,7 +370,7 @@ static const Param* find_param(const wmdec_decoder* d, const char* name) {
 
 // layout of the workspace for `batch` frames
 struct WsLayout {
-  size_t tickets, act[3], qkv, vt, attn_o, attn_scratch, mean, rstd, stats_ws, stats_ws_bytes, total;
+  size_t tickets, conv_tickets, conv_ticket_bytes, rows[2], act[3], qkv, vt, attn_o, attn_scratch, mean, rstd, stats_ws, stats_ws_bytes, total;
 };
 
 static WsLayout ws_layout(const wmdec_decoder* d, int batch) {
@@ -352,6 +379,19 @@ static WsLayout ws_layout(const wmdec_decoder* d, int batch) {
   const size_t act = align_up(d->act_elems_per_frame * es * batch, 256);
   size_t o = 0;
   L.tickets = o; o += gn_stats_ticket_bytes(d->cfg.max_batch);   // same place and size for every batch: zeroed once
+  // ticket counters and row moments of the convolutions that hand their statistics over without a merge launch (sized
+  // for max_batch, like the counters above: they are zeroed once per workspace and return to zero by themselves)
+  size_t max_tickets = 0, max_rows = 0;
+  for (const Step& st : d->steps) {
+    if (st.kind != Step::CONV || st.emit_rows < 0) continue;
+    int rows = 0, ctiles = 0, per_row = 0;
+    conv_mfma_row_extents(step_shape_args(*d, st, 1), &rows, &ctiles, &per_row);
+    if ((size_t)rows * ctiles > max_tickets) max_tickets = (size_t)rows * ctiles;
+    if ((size_t)rows > max_rows) max_rows = rows;
+  }
+  L.conv_ticket_bytes = align_up(max_tickets * d->cfg.max_batch * sizeof(unsigned), 256);
+  L.conv_tickets = o; o += L.conv_ticket_bytes;
+  for (int i = 0; i < 2; ++i) { L.rows[i] = o; o += align_up(max_rows * d->cfg.max_batch * d->cfg.groups * 3 * sizeof(float), 256); }
   for (int i = 0; i < 3; ++i) { L.act[i] = o; o += act; }
   L.qkv = o; o += align_up((size_t)batch * d->attn_t * 3 * d->attn_c * es, 256);
   L.vt = o; o += align_up((size_t)batch * d->attn_c * d->attn_tpad * es, 256);
@@ -664,7 +704,7 @@ void decoder_default_config(wmdec_decoder_config* cfg) {
   cfg->resblocks_per_level = 3;
   cfg->groups = 32; cfg->eps = 1e-6f; cfg->out_c = 3;
   cfg->act_dtype = WMDEC_F16; cfg->max_batch = 4;
-  cfg->latent_dtype = WMDEC_BF16; cfg->separate_stats_pass = 0; cfg->separate_shortcut = 0;
+  cfg->latent_dtype = WMDEC_BF16; cfg->separate_stats_pass = 0; cfg->separate_shortcut = 0; cfg->separate_merge_launch = 0;
 }
 
 int decoder_create(const wmdec_decoder_config* cfg, wmdec_decoder** out) {
@@ -800,7 +840,11 @@ static int launch_step(wmdec_decoder* dec, const WsLayout& L, const Step& st, co
         if (st.src == BUF_LATENT) { a.x = latent.z; a.x_dtype = c.latent_dtype; a.x_nchw = 1; a.x_step = latent.step; a.step_scale = latent.scale; }
         else if (st.to_attn == 2) { a.x = ws + L.attn_o; a.x_dtype = c.act_dtype; }
         else { a.x = buf(st.src); a.x_dtype = c.act_dtype; }
-        if (st.norm) { a.mean = mean; a.rstd = rstd; a.gamma = (const float*)(pk + st.gamma_off); a.beta = (const float*)(pk + st.beta_off); a.groups = c.groups; a.silu = st.silu; }
+        if (st.norm) {
+          a.gamma = (const float*)(pk + st.gamma_off); a.beta = (const float*)(pk + st.beta_off); a.groups = c.groups; a.silu = st.silu;
+          if (st.rows_from >= 0) { a.rows_in = ws + L.rows[st.rows_from]; a.rows_in_count = st.rows_count; a.eps = c.eps; }
+          else { a.mean = mean; a.rstd = rstd; }
+        }
         a.wt = pk + st.w_off; a.bias = (const float*)(pk + st.b_off);
         if (st.upsample) a.wt_phase = pk + st.w_off + upconv_phase_offset_bytes(st.cout, st.cin, c.act_dtype);
         a.res = buf(st.res);
@@ -813,6 +857,7 @@ static int launch_step(wmdec_decoder* dec, const WsLayout& L, const Step& st, co
           a.stats_groups = c.groups;
           (*emitted_slots) = conv_mfma_stats_slots(a);
           if ((*emitted_slots) > 0) a.stats_ws = ws + L.stats_ws;
+          if (st.emit_rows >= 0) { a.rows_out = ws + L.rows[st.emit_rows]; a.tickets = ws + L.conv_tickets; }
         }
         rc = launch_conv(a, s);
         break;
@@ -824,6 +869,7 @@ static int launch_step(wmdec_decoder* dec, const WsLayout& L, const Step& st, co
                               (size_t)3 * st.cin, (size_t)t * 3 * st.cin, (size_t)dec->attn_tpad, (size_t)st.cin * dec->attn_tpad, s);
         break;
       }
+      case Step::NONE: break;
       case Step::FLASH: {
         const size_t es = dtype_size(c.act_dtype);
         const int t = st.h * st.w;
@@ -848,7 +894,7 @@ static int run_graph(const char* who, wmdec_decoder* dec, const LatentSource& la
   hipStream_t s = (hipStream_t)stream;
   char* ws = (char*)dec->ws;
   if (dec->ws_fresh) {   // once per workspace: the ticket counter of the statistics kernel starts at zero
-    const int rc0 = launch_zero_u32(ws + L.tickets, (int)(gn_stats_ticket_bytes(dec->cfg.max_batch) / 4), s);
+    const int rc0 = launch_zero_u32(ws + L.tickets, (int)((gn_stats_ticket_bytes(dec->cfg.max_batch) + L.conv_ticket_bytes) / 4), s);
     if (rc0 != WMDEC_OK) return rc0;
     dec->ws_fresh = false;
   }
@@ -946,6 +992,7 @@ int decoder_step_info(const wmdec_decoder* dec, int index, const char** kernel, 
       case Step::STATS: *kernel = st.from_producer ? "gn_finalize" : "gn_stats_vec"; break;
       case Step::QKV_TRANSPOSE_V: *kernel = "transpose_kernel"; break;
       case Step::FLASH: *kernel = "flash_attn_kernel"; break;
+      case Step::NONE: *kernel = ""; break;
       case Step::CONV: {
         ConvArgs a = step_shape_args(*dec, st, 1);   // only the fields the kernel choice looks at
         a.groups_norm = st.norm; a.silu = st.silu;

@@ -97,6 +97,12 @@ struct ConvArgs {
   int cin2 = 0;
   void* stats_ws = nullptr;      // non-null: also emit GroupNorm moments of y, [n][stats_groups][slots] triples
   int stats_groups = 0;
+  // matrix-core kernel only: statistics handed from producer to consumer without a merge launch
+  void* rows_out = nullptr;      // non-null (with stats_ws, tickets): one triple per (sample, group, tile row) of y
+  void* tickets = nullptr;       // zeroed counters, one per (sample, tile row, channel tile); left at zero
+  const void* rows_in = nullptr; // non-null instead of mean / rstd: row triples of x, [n][groups][rows_in_count]
+  int rows_in_count = 0;
+  float eps = 0.f;               // with rows_in: rstd = 1/sqrt(var + eps)
 };
 
 // kernels_conv_direct.hip: general VALU convolution (any shape, all dtypes).
@@ -112,6 +118,7 @@ int launch_conv_mfma(const ConvArgs& a, hipStream_t s);
 bool conv_mfma_uses_phase(const ConvArgs& a);
 // moment slots per (sample, group) the MFMA kernel would write for this launch; 0: it cannot emit statistics
 int conv_mfma_stats_slots(const ConvArgs& a);
+void conv_mfma_row_extents(const ConvArgs& a, int* tile_rows, int* channel_tiles, int* tiles_per_row);
 const char* conv_mfma_label(const ConvArgs& a);   // instantiation name, valid until the thread's next call
 // picks the kernel
 int launch_conv(const ConvArgs& a, hipStream_t s);

@@ -44,6 +44,12 @@ struct MfmaParams {
   int y_nchw;                    // 1: y is planar [n][cout][h][w] (the frame), else NHWC
   Moments* stats;                // non-null: moments of y per (sample, group, slot); slot = spatial tile * WM + wave row
   int stats_cpg, stats_groups, stats_slots;
+  // Statistics hand-over without a merge launch.  rows_out: the last workgroup of every (sample, tile row, channel
+  // tile) merges that row's triples into one triple per group, [n][stats_groups][tiles_y]; tickets: one counter per
+  // (sample, tile row, channel tile), zero before the launch and zero again after it.  rows_in: the statistics of x
+  // arrive as such row triples, [n][groups][rows_in_count], and are merged while the scale/shift table is built.
+  Moments* rows_out; unsigned* tickets;
+  const Moments* rows_in; int rows_in_count; float eps;
   // 1x1 shortcut folded into the contraction (3x3 only): y += W2 * x2 + bias2, x2 [n,h,w,cin2] taken as stored
   const void* x2; const void* w2; const float* bias2;
   int cin2, w2_bytes;
@@ -206,7 +212,8 @@ __device__ __forceinline__ void epilogue_store(const f32x16 (&acc)[MI][NI], floa
     }
     // channels of one group are cpg consecutive lanes
     for (int mask = 1; mask < cpg; mask <<= 1) m = butterfly(m, lane, mask);
-    if (lane < CV * 8 && (lane & (cpg - 1)) == 0) stats[(size_t)((co_w + lane) / cpg) * stats_stride] = m;
+    // (device-scope stores: another workgroup of this launch may merge them, see the row hand-over in the kernel)
+    if (lane < CV * 8 && (lane & (cpg - 1)) == 0) store_device(stats + (size_t)((co_w + lane) / cpg) * stats_stride, m);
   }
 }
 
@@ -532,10 +539,38 @@ void conv_mfma_kernel(MfmaParams p) {
   if constexpr (ACT > 0) {
     const int cpg = p.cin / p.groups;
     const float k = ACT == 2 ? -1.4426950408889634f : 1.0f;
-    for (int c = tid; c < p.cin; c += NT) {
-      const int g = c / cpg;
-      const float a = p.gamma[c] * p.rstd[n * p.groups + g];
-      s_ab[c] = make_float2(k * a, k * (p.beta[c] - p.mean[n * p.groups + g] * a));
+    if (p.rows_in) {
+      // mean / rstd of every group from the row triples its producer left: eight lanes per group take the rows
+      // round-robin in order, then a fixed butterfly; (mean, rstd) parked behind the table
+      float2* s_stat = s_ab + p.cin;
+      const int sub = tid & 7;
+      for (int g = tid >> 3; g < p.groups; g += NT / 8) {
+        const Moments* row = p.rows_in + (size_t)(n * p.groups + g) * p.rows_in_count;
+        Moments t[8];       // at most 64 rows (checked on the host): all loads in flight before the first merge
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const int r = sub + 8 * k;
+          t[k] = row[min(r, p.rows_in_count - 1)];
+          if (r >= p.rows_in_count) t[k].n = 0.f;
+        }
+        Moments m = t[0];
+#pragma unroll
+        for (int k = 1; k < 8; ++k) m = merge(m, t[k]);
+        for (int mask = 1; mask < 8; mask <<= 1) m = butterfly(m, lane, mask);
+        if (sub == 0) s_stat[g] = make_float2(m.mean, 1.0f / sqrtf(m.m2 / m.n + p.eps));
+      }
+      __syncthreads();
+      for (int c = tid; c < p.cin; c += NT) {
+        const float2 st = s_stat[c / cpg];
+        const float a = p.gamma[c] * st.y;
+        s_ab[c] = make_float2(k * a, k * (p.beta[c] - st.x * a));
+      }
+    } else {
+      for (int c = tid; c < p.cin; c += NT) {
+        const int g = c / cpg;
+        const float a = p.gamma[c] * p.rstd[n * p.groups + g];
+        s_ab[c] = make_float2(k * a, k * (p.beta[c] - p.mean[n * p.groups + g] * a));
+      }
     }
   }
   __syncthreads();            // scale/shift table complete
@@ -595,6 +630,41 @@ void conv_mfma_kernel(MfmaParams p) {
     epilogue_store<T, TO, MI, NI, MTW, MTH, MT_PER_ROW, false>(acc, patch, lane, PH ? 0 : wm * MI, ty0, tx0, co0 + wn * NI * 32, p.bias,
                                                                p.bias2, rin, yout, p.h, p.w_out, p.cout, p.y_nchw != 0, st, p.stats_cpg, p.stats_slots,
                                                                PH ? 2 : 1, PH ? wave >> 1 : 0, PH ? wave & 1 : 0);
+
+  // ---- row hand-over: the workgroup that finishes a (sample, tile row, channel tile) last merges the row's triples.
+  // Same protocol as the single-launch statistics kernel: the triples were written with device-scope stores, every
+  // wavefront waits for its stores, the workgroup takes a ticket (a wrapping counter that returns to zero by itself),
+  // and only the last one reads, with device-scope loads, in a fixed order.
+  if (p.rows_out) {
+    __shared__ unsigned s_last;
+    wait_stores();
+    __syncthreads();
+    const int tile_y = tile / p.tiles_x;
+    if (tid == 0) s_last = atomicInc(p.tickets + ((size_t)n * p.tiles_y + tile_y) * p.ntiles + nt, p.tiles_x - 1) == (unsigned)(p.tiles_x - 1);
+    __syncthreads();
+    if (s_last) {
+      const int per_row = p.tiles_x * WM;                  // triples of one group in this tile row
+      const int g0 = co0 / p.stats_cpg, gcount = min(TN, p.cout - co0) / p.stats_cpg;
+      const int sub = tid & 7;
+      for (int gi = tid >> 3; gi < gcount; gi += NT / 8) {
+        const Moments* src = p.stats + ((size_t)n * p.stats_groups + g0 + gi) * p.stats_slots + (size_t)tile_y * per_row;
+        Moments m{0.f, 0.f, 0.f};
+        for (int e0 = sub; e0 < per_row; e0 += 64) {     // eight loads in flight per lane
+          Moments t[8];
+#pragma unroll
+          for (int k = 0; k < 8; ++k) {
+            const int e = e0 + 8 * k;
+            t[k] = load_device(src + min(e, per_row - 1));
+            if (e >= per_row) t[k].n = 0.f;
+          }
+#pragma unroll
+          for (int k = 0; k < 8; ++k) m = merge(m, t[k]);
+        }
+        for (int mask = 1; mask < 8; mask <<= 1) m = butterfly(m, lane, mask);
+        if (sub == 0) p.rows_out[((size_t)n * p.stats_groups + g0 + gi) * p.tiles_y + tile_y] = m;
+      }
+    }
+  }
 }
 
 template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC, bool PH = false>
@@ -614,6 +684,11 @@ int launch_cfg(const ConvArgs& a, hipStream_t s) {
   p.w_bytes = (int)(packed_elems(PH ? 16 : KS * KS, a.cout, a.cin) * sizeof(T));
   p.stats = (Moments*)a.stats_ws; p.stats_groups = a.stats_groups; p.stats_cpg = a.stats_groups > 0 ? a.cout / a.stats_groups : 1;
   p.stats_slots = p.tiles_x * p.tiles_y * WM;
+  p.rows_out = (Moments*)a.rows_out; p.tickets = (unsigned*)a.tickets;
+  p.rows_in = (const Moments*)a.rows_in; p.rows_in_count = a.rows_in_count; p.eps = a.eps;
+  WMDEC_REQUIRE(!p.rows_out || (p.stats && p.tickets), WMDEC_ERR_INVALID_ARG, "conv_mfma: row moments need the triple scratch and the ticket counters");
+  WMDEC_REQUIRE(!p.rows_in || (p.rows_in_count >= 1 && p.rows_in_count <= 64), WMDEC_ERR_UNSUPPORTED, "conv_mfma: at most 64 rows of moments can be merged in the prologue");
+  p.norm = a.mean != nullptr || a.rows_in != nullptr;
   p.x2 = nullptr; p.w2 = nullptr; p.bias2 = nullptr; p.cin2 = 0; p.w2_bytes = 0;
   if (a.x2) {
     WMDEC_REQUIRE(KS == 3 && !PH && a.w2 && a.cin2 > 0 && a.cin2 % KC == 0 && (long)a.h * a.w * a.cin2 < (1L << 29), WMDEC_ERR_UNSUPPORTED,
@@ -622,7 +697,7 @@ int launch_cfg(const ConvArgs& a, hipStream_t s) {
     p.w2_bytes = (int)(packed_elems(1, a.cout, a.cin2) * sizeof(T));
   }
   constexpr int NT = 64 * WM * WN;
-  size_t smem = (((size_t)2 * tile_buf_elems(TH, TW, PAD, KC) * 2 + 15) & ~(size_t)15) + (size_t)a.cin * sizeof(float2);
+  size_t smem = (((size_t)2 * tile_buf_elems(TH, TW, PAD, KC) * 2 + 15) & ~(size_t)15) + (size_t)(a.cin + a.groups) * sizeof(float2);
   const size_t patch = (size_t)(WM * WN) * patch_floats(NI) * sizeof(float);   // epilogue patches of the wavefronts
   if (smem < patch) smem = patch;
   WMDEC_REQUIRE(smem <= 80 * 1024, WMDEC_ERR_UNSUPPORTED, "conv_mfma: %zu bytes of LDS needed", smem);
@@ -742,6 +817,16 @@ int conv_mfma_stats_slots(const ConvArgs& a) {
   return ((w_t + ts.tw - 1) / ts.tw) * ((h_t + ts.th - 1) / ts.th) * ts.wm;
 }
 
+// tile rows / channel tiles of a launch: the extents of the row moments it can leave and of its ticket counters
+void conv_mfma_row_extents(const ConvArgs& a, int* tile_rows, int* channel_tiles, int* tiles_per_row) {
+  const TileId t = pick_tile(a);
+  const TileShape& ts = kTiles[t];
+  const int h_t = t == T_PHASE ? a.h / 2 : a.h, w_t = t == T_PHASE ? a.w / 2 : a.w, tn = ts.wn * ts.ni * 32;
+  *tile_rows = (h_t + ts.th - 1) / ts.th;
+  *channel_tiles = (a.cout + tn - 1) / tn;
+  *tiles_per_row = (w_t + ts.tw - 1) / ts.tw;
+}
+
 // the instantiation a launch would use, spelled like a profiler prints it
 const char* conv_mfma_label(const ConvArgs& a) {
   static thread_local char buf[160];
@@ -749,7 +834,7 @@ const char* conv_mfma_label(const ConvArgs& a) {
   const int kc = a.ksize == 1 ? chunk_1x1(a) : 32;
   const TileShape& ts = kTiles[t];
   const char* ty = a.op_dtype == WMDEC_BF16 ? "wmdec::bf16_t" : "wmdec::f16_t";
-  const int act = a.mean == nullptr && !a.groups_norm ? 0 : (a.silu ? 2 : 1);
+  const int act = a.mean == nullptr && a.rows_in == nullptr && !a.groups_norm ? 0 : (a.silu ? 2 : 1);
   snprintf(buf, sizeof(buf), "conv_mfma_kernel<%s, %s, %d, %d, %d, %d, %d, %d, %d, %d, %s>", ty,
            a.y_dtype == WMDEC_F32 ? "float" : ty, ts.th, ts.tw, ts.wm, ts.wn, ts.ni, a.ksize, kc, act, t == T_PHASE ? "true" : "false");
   return buf;

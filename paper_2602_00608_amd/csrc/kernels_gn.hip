@@ -43,27 +43,6 @@ template <> struct alignas(16) Vec16<f16_t> { static constexpr int N = 8; f16_t 
 // adds the threads of a channel in a fixed order through LDS, the channels of a group with a butterfly, and
 // writes one triple per group.  The workgroup of a sample that finishes last (one wrapping ticket counter per
 // sample, which returns to zero by itself) merges the sample's triples in a fixed order into mean / rstd.
-// device-scope (write-through / L2-bypassing) accesses of a triple, and the wait that orders them before a ticket
-__device__ __forceinline__ void store_device(Moments* p, Moments m) {
-  __hip_atomic_store(&p->n, m.n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  __hip_atomic_store(&p->mean, m.mean, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  __hip_atomic_store(&p->m2, m.m2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ Moments load_device(const Moments* p) {
-  Moments m;
-  m.n = __hip_atomic_load(&p->n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  m.mean = __hip_atomic_load(&p->mean, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  m.m2 = __hip_atomic_load(&p->m2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  return m;
-}
-__device__ __forceinline__ void wait_stores() {
-  __builtin_amdgcn_sched_barrier(0);
-  // s_waitcnt immediate of gfx9-family chips: vmcnt in bits 3:0 and 15:14, expcnt in 6:4, lgkmcnt in 11:8
-  constexpr int kVmcnt0 = 0, kExpcntAny = 7 << 4, kLgkmcntAny = 0xF << 8;
-  __builtin_amdgcn_s_waitcnt(kVmcnt0 | kExpcntAny | kLgkmcntAny);   // every store of this wavefront has been acknowledged
-  __builtin_amdgcn_sched_barrier(0);
-}
-
 constexpr int kVecThreads = 1024;
 constexpr int kVecMaxChunks = 256;
 constexpr int kVecMaxGroups = 256;

@@ -30,7 +30,7 @@ class DecoderConfig(ctypes.Structure):
                 ("resblocks_per_level", ctypes.c_int), ("groups", ctypes.c_int), ("eps", ctypes.c_float),
                 ("out_c", ctypes.c_int), ("act_dtype", ctypes.c_int), ("max_batch", ctypes.c_int),
                 ("latent_dtype", ctypes.c_int), ("separate_stats_pass", ctypes.c_int),
-                ("separate_shortcut", ctypes.c_int)]
+                ("separate_merge_launch", ctypes.c_int), ("separate_shortcut", ctypes.c_int)]
 
 
 _vp, _i, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t

@@ -408,6 +408,34 @@ def test_statistics_from_the_epilogue_match_the_statistics_pass():
     assert ref.rel_err(outs[0], outs[1]) <= G.TOL["f16"], ref.rel_err(outs[0], outs[1])
 
 
+def test_statistics_hand_over_without_a_merge_launch():
+    """Default graph: the last workgroup of every tile row of the producing convolution merges that row's partial
+    moments, the consuming convolution merges the rows while it builds its scale/shift table.  Against the graph with
+    the merge launch: 29 launches fewer on the full decoder, both within the bar of the oracle, and the hand-over
+    (device-scope stores, a ticket per tile row) gives the same bits on every repetition."""
+    chans = (512, 128, 64, 64)
+    spec = synth.decoder_weight_spec(level_channels=chans, resblocks_per_level=2)
+    weights = synth.draw_params(spec, synth.weight_seed(11), random_affine=True)
+    z = synth.latent_sequence(workload=11, frames=3, h=9, w=11)
+    want = ref.decoder(z, weights, level_channels=chans, resblocks_per_level=2, groups=32, eps=1e-6)
+    outs = {}
+    for separate in (0, 1):
+        cfg = small_cfg(wmdec.F16)
+        cfg.latent_h, cfg.latent_w = 9, 11
+        cfg.level_channels[3] = 64
+        cfg.separate_merge_launch = separate
+        outs[separate] = run_decoder(cfg, weights, z)
+        assert ref.rel_err(outs[separate], want) <= G.TOL["f16"], separate
+        for _ in range(3):
+            assert np.array_equal(run_decoder(cfg, weights, z), outs[separate])
+    assert ref.rel_err(outs[0], outs[1]) <= G.TOL["f16"]
+    # a frame's bits do not depend on the batch it is decoded in
+    cfg = small_cfg(wmdec.F16)
+    cfg.latent_h, cfg.latent_w = 9, 11
+    cfg.level_channels[3] = 64
+    assert np.array_equal(run_decoder(cfg, weights, z[2:3])[0], outs[0][2])
+
+
 def test_folded_shortcut_against_separate_shortcut_and_the_oracle():
     """The 1x1 shortcut of the channel-changing ResBlocks as extra contraction steps of the second convolution
     (default) and as a launch of its own: both graphs against the oracle; fewer launches with the fold."""
