@@ -196,6 +196,25 @@ def extrapolated_latents(z_prev, v_prev, lam, hits):
     return np.stack(out) if out else np.empty((0,) + z.shape)
 
 
+def adaln_modulation(c, p, apply_silu=True):
+    """The AdaLN block's three small projections of the conditioning vector as the unfused graph runs them
+    (Sec. IV-B-2: one small product per parameter): with a = SiLU(c) (the usual activation in front of the
+    modulation; a = c if apply_silu is false),
+        shift = W_shift a + b_shift,   scale = W_scale a + b_scale,   gate = W_gate a + b_gate.
+    c: [batch, d_cond]; p maps 'shift.w', 'scale.w', 'gate.w' ([d_model, d_cond]) and '.b' ([d_model]).
+    Returns (shift, scale, gate), each [batch, d_model].  Horizontal fusion stores the three matrices as one block
+    and runs one product; it must return exactly these values, concatenated."""
+    a = silu(c) if apply_silu else _f64(c)
+    out = []
+    for name in ("shift", "scale", "gate"):
+        w, b = _f64(p[name + ".w"]), _f64(p[name + ".b"])
+        y = np.empty((a.shape[0], w.shape[0]))
+        for i in range(a.shape[0]):          # one matrix-vector product per conditioning vector and parameter
+            y[i] = w @ a[i] + b
+        out.append(y)
+    return tuple(out)
+
+
 def rel_err(got, want):
     """max|got-want| / rms(want): the comparison metric of every parity test."""
     want = np.asarray(want, dtype=np.float64)

@@ -143,6 +143,17 @@ def latent_sequence(workload=5, frames=4, h=LATENT_H, w=LATENT_W, c=LATENT_C):
     return bf16_round(z)
 
 
+def adaln_params(seed, d_model, d_cond, sixteen_bit=True):
+    """Weights of one AdaLN modulation: 'shift.w', 'scale.w', 'gate.w' ~ N(0, std=1/sqrt(d_cond)) [d_model, d_cond]
+    (16-bit storage when asked) and their biases ~ N(0, std=0.01), drawn in that order."""
+    rng = np.random.default_rng(seed)
+    out = {}
+    for name in ("shift", "scale", "gate"):
+        out[name + ".w"] = normal(rng, (d_model, d_cond), 1.0 / math.sqrt(d_cond), sixteen_bit)
+        out[name + ".b"] = normal(rng, (d_model,), 0.01)
+    return out
+
+
 def activation(workload, shape, sixteen_bit):
     rng = np.random.default_rng(input_seed(workload))
     return normal(rng, shape, 1.0, sixteen_bit)

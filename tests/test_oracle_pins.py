@@ -409,6 +409,43 @@ def test_latent_extrapolation_pins():
     assert np.allclose(half[1], ref.latent_extrapolate(z, v, 1.0), atol=1e-15)
 
 
+def test_adaln_modulation_pins():
+    """Sec. IV-B-2: three small projections of one conditioning vector.  Brute-force loops on a tiny case; identity
+    matrices return the activated vector itself; SiLU(0) = 0 leaves only the biases; each output is linear in its own
+    matrix and blind to the other two; and the row-concatenated matrix in ONE product (what horizontal fusion runs)
+    gives the three results side by side."""
+    r = np.random.default_rng(88)
+    b, dc, dm = 3, 5, 4
+    c = r.standard_normal((b, dc))
+    p = {n + s: r.standard_normal((dm, dc) if s == ".w" else (dm,)) for n in ("shift", "scale", "gate") for s in (".w", ".b")}
+    got = ref.adaln_modulation(c, p, apply_silu=True)
+    for k, name in enumerate(("shift", "scale", "gate")):
+        want = np.empty((b, dm))
+        for i in range(b):
+            for j in range(dm):
+                acc = p[name + ".b"][j]
+                for t in range(dc):
+                    x = c[i, t]
+                    acc += p[name + ".w"][j, t] * (x / (1.0 + math.exp(-x)))
+                want[i, j] = acc
+        assert np.allclose(got[k], want, rtol=0, atol=1e-13)
+    eye = {n + ".w": np.eye(dc) for n in ("shift", "scale", "gate")}
+    eye.update({n + ".b": np.zeros(dc) for n in ("shift", "scale", "gate")})
+    for y in ref.adaln_modulation(c, eye, apply_silu=False):
+        assert np.array_equal(y, c)
+    for k, name in enumerate(("shift", "scale", "gate")):
+        assert np.allclose(ref.adaln_modulation(np.zeros((2, dc)), p)[k], np.tile(p[name + ".b"], (2, 1)), atol=1e-15)
+    q = dict(p)
+    q["scale.w"] = 2.0 * p["scale.w"]
+    got2 = ref.adaln_modulation(c, q)
+    assert np.array_equal(got2[0], got[0]) and np.array_equal(got2[2], got[2])
+    assert np.allclose(got2[1] - p["scale.b"], 2.0 * (got[1] - p["scale.b"]), atol=1e-13)
+    w_fused = np.vstack([p["shift.w"], p["scale.w"], p["gate.w"]])
+    b_fused = np.concatenate([p["shift.b"], p["scale.b"], p["gate.b"]])
+    one = ref.silu(c) @ w_fused.T + b_fused
+    assert np.allclose(one, np.hstack(got), rtol=0, atol=1e-13)
+
+
 def test_rel_err_metric():
     want = np.array([3.0, -4.0])
     assert abs(ref.rel_err(want + np.array([0.0, 0.5]), want) - 0.5 / math.sqrt(12.5)) < 1e-15
