@@ -230,6 +230,31 @@ int wmdec_attention(const void* x, int act_dtype, const float* mean, const float
                     void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * Horizontal fusion for the DiT's AdaLN block (Sec. IV-B-2).  A block's
+ * modulation vectors are three small products of the same conditioning vector,
+ *   shift = W_shift a + b_shift,  scale = W_scale a + b_scale,  gate = W_gate a + b_gate,
+ * a = SiLU(c) if apply_silu else c.  With the matrices stored as one
+ * row-concatenated block W_fused = [W_shift; W_scale; W_gate] (and likewise the
+ * biases) they are one product and one launch:
+ *   out[b, j] = bias[j] + sum_k W_fused[j, k] * a[b, k],   j < rows, k < d_cond,
+ * so rows = 3 * d_model (any number of row blocks works: the call does not
+ * care where one matrix ends).  c: [batch, d_cond] of c_dtype; w_fused:
+ * row-major [rows, d_cond] of w_dtype (no packing); bias: fp32 [rows] or NULL;
+ * out: fp32 [batch, rows], so shift, scale, gate of sample b are the three
+ * thirds of row b.  Products and sums in fp32.
+ * With a few conditioning vectors per call (one per frame) this is bound by
+ * the one read of the weights from HBM, not by arithmetic; the conditioning
+ * vectors are held in LDS, which limits a call to wmdec_adaln_max_batch(d_cond)
+ * of them (the largest power of two <= 16 with batch * d_cond <= 16384, e.g. 8
+ * for d_cond = 1920); beyond: WMDEC_ERR_UNSUPPORTED.  d_cond must be a multiple
+ * of 8 and at most 4096 (16-bit weights), or a multiple of 4 and at most 2048
+ * (F32). */
+int wmdec_adaln_max_batch(int d_cond);
+int wmdec_adaln_fused_projection(const void* c, int c_dtype, const void* w_fused, int w_dtype,
+                                 const float* bias, float* out, int batch, int d_cond, int rows,
+                                 int apply_silu, void* stream);
+
+/* ------------------------------------------------------------------------
  * Whole decoder:  latent z[N,latent_c,h,w] -> frame [N,out_c,8h,8w]
  * (the I_t <- VAE_Decode(z_t) step of Alg. 1 / Alg. 2).
  * Graph: conv_in 3x3; mid = ResBlock, attention, ResBlock; per level

@@ -95,10 +95,10 @@ def main():
              (512, 256, 240, 360, 3, 0, 1, 0), (512, 512, 120, 180, 3, 0, 1, 1), (512, 512, 60, 90, 3, 0, 1, 1),
              (256, 256, 480, 720, 3, 1, 0, 0), (512, 512, 240, 360, 3, 1, 0, 0), (512, 512, 120, 180, 3, 1, 0, 0),
              (256, 128, 480, 720, 1, 0, 0, 0), (512, 256, 240, 360, 1, 0, 0, 0), (512, 1536, 60, 90, 1, 0, 1, 0),
-             (128, 3, 480, 720, 3, 0, 1, 0)]
+             ]
     for cin, cout, h, w, k, ups, norm, use_res in convs:
         hi, wi = (h // 2, w // 2) if ups else (h, w)
-        out_dt = torch.float32 if cout == 3 else dt          # conv_out writes the fp32 frame
+        out_dt = dt
         x = torch.randn((1, hi, wi, cin), device="cuda").to(dt)
         y = torch.empty((1, h, w, cout), device="cuda", dtype=out_dt)
         res = torch.randn((1, h, w, cout), device="cuda").to(dt) if use_res else None
@@ -140,6 +140,26 @@ def main():
     y = torch.empty((1, 240, 360, 256), device="cuda", dtype=dt)
     us = timeit(lambda: wmdec.upsample2x_nearest(x, y), args.reps)
     line("upsample2x_nearest", "%4d       @%3dx%3d" % (256, 240, 360), us, (x.numel() + y.numel()) * 2, "GB/s", PEAK_GBPS)
+
+
+    # horizontally fused AdaLN projections: one launch on [W_shift; W_scale; W_gate] against three launches
+    d = 1920
+    for batch in (1, 4):
+        c = torch.randn((batch, d), device="cuda")
+        wf = (torch.randn((3 * d, d), device="cuda") / d ** 0.5).to(torch.bfloat16)
+        bf = 0.01 * torch.randn(3 * d, device="cuda")
+        out = torch.empty((batch, 3 * d), device="cuda")
+        parts = [wf[i * d:(i + 1) * d].contiguous() for i in range(3)]
+        outs = [torch.empty((batch, d), device="cuda") for _ in range(3)]
+        fused = timeit(lambda: wmdec.adaln_fused_projection(c, wf, bf, out), args.reps)
+
+        def three():
+            for i in range(3):
+                wmdec.adaln_fused_projection(c, parts[i], bf[i * d:(i + 1) * d], outs[i])
+        sep = timeit(three, args.reps)
+        nbytes = wf.numel() * 2
+        line("adaln fused (1 launch)", "batch %d %d->3x%d" % (batch, d, d), fused, nbytes, "GB/s", PEAK_GBPS)
+        line("adaln 3 launches", "batch %d %d->3x%d" % (batch, d, d), sep, nbytes, "GB/s", PEAK_GBPS)
 
 
 if __name__ == "__main__":

@@ -10,7 +10,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libwmdec.so")
 
 SOURCES = ["api.cpp", "kernels_gn.hip", "kernels_conv_direct.hip", "kernels_conv_mfma.hip",
-           "kernels_misc.hip", "kernels_attn.hip"]
+           "kernels_misc.hip", "kernels_attn.hip", "kernels_adaln.hip"]
 
 FLAGS = ["-x", "hip", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

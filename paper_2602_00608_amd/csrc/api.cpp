@@ -694,6 +694,25 @@ int wmdec_attention(const void* x, int act_dtype, const float* mean, const float
                         ws + qo, ws + vo, ws + oo, ws + so, (hipStream_t)stream);
 }
 
+// ---- horizontally fused AdaLN projections
+int wmdec_adaln_max_batch(int d_cond) { return adaln_max_batch(d_cond); }
+
+int wmdec_adaln_fused_projection(const void* c, int c_dtype, const void* w_fused, int w_dtype, const float* bias, float* out,
+                                 int batch, int d_cond, int rows, int apply_silu, void* stream) {
+  WMDEC_REQUIRE(c && w_fused && out, WMDEC_ERR_INVALID_ARG, "adaln_fused_projection: null pointer");
+  WMDEC_REQUIRE(valid_dtype(c_dtype) && valid_dtype(w_dtype), WMDEC_ERR_INVALID_ARG, "adaln_fused_projection: bad dtype");
+  WMDEC_REQUIRE(batch > 0 && d_cond > 0 && rows > 0, WMDEC_ERR_INVALID_ARG, "adaln_fused_projection: non-positive size");
+  WMDEC_REQUIRE(aligned16(c) && aligned16(w_fused) && aligned16(out), WMDEC_ERR_INVALID_ARG, "adaln_fused_projection: pointers must be 16-byte aligned");
+  WMDEC_REQUIRE(d_cond % (int)(16 / dtype_size(w_dtype)) == 0 && d_cond % (int)(16 / dtype_size(c_dtype)) == 0, WMDEC_ERR_SHAPE,
+                "adaln_fused_projection: d_cond %d must be a multiple of 8 for 16-bit operands and of 4 for F32 (16-byte vectors)", d_cond);
+  WMDEC_REQUIRE(d_cond <= adaln_max_d_cond(w_dtype), WMDEC_ERR_UNSUPPORTED, "adaln_fused_projection: d_cond %d above the limit of %d for this weight type",
+                d_cond, adaln_max_d_cond(w_dtype));
+  WMDEC_REQUIRE(batch <= adaln_max_batch(d_cond), WMDEC_ERR_UNSUPPORTED,
+                "adaln_fused_projection: at most %d conditioning vectors of length %d per call (they are held in LDS); "
+                "larger batches are a GEMM: use wmdec_gn_conv1x1 on a [1,1,batch,d_cond] tensor", adaln_max_batch(d_cond), d_cond);
+  return launch_adaln_projection(c, c_dtype, w_fused, w_dtype, bias, out, batch, d_cond, rows, apply_silu ? 1 : 0, (hipStream_t)stream);
+}
+
 // ---- decoder
 void decoder_default_config(wmdec_decoder_config* cfg) {
   if (!cfg) return;

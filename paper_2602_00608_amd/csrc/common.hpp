@@ -156,6 +156,12 @@ int launch_copy_f32(const float* src, float* dst, size_t count, hipStream_t s);
 int launch_axpy(const void* z, const void* v, int dtype, float scale, void* out, int out_dtype, size_t count, hipStream_t s);
 int launch_zero_u32(void* p, int count, hipStream_t s);   // a fill kernel (safe under graph capture, unlike a memset node)
 
+// kernels_adaln.hip: out[b][j] = bias[j] + sum_k w[j][k] * act(c[b][k]); w row-major [rows][d_cond], out fp32 [batch][rows]
+int adaln_max_batch(int d_cond);   // conditioning vectors one launch can take (they are held in LDS)
+int adaln_max_d_cond(int w_dtype);  // longest conditioning vector (a lane keeps a row's weights in registers)
+int launch_adaln_projection(const void* c, int c_dtype, const void* w, int w_dtype, const float* bias, float* out, int batch,
+                            int d_cond, int rows, int apply_silu, hipStream_t s);
+
 // kernels_attn.hip
 // q,k: [n][t][ld] rows of d elements (16-bit type), vt: [n][d][t_pad] keys contiguous, o: [n][t][d]
 // scratch: flash_attention_scratch_bytes(n, t, d) bytes (partial outputs of the key splits), may be null if 0

@@ -59,6 +59,8 @@ SIGNATURES = {
     "wmdec_nhwc_to_nchw": (_i, [_vp, _i, _vp, _i, _i, _i, _i, _i, _vp]),
     "wmdec_attention_workspace_bytes": (_sz, [_i] * 4),
     "wmdec_attention": (_i, [_vp, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp, _sz, _vp]),
+    "wmdec_adaln_max_batch": (_i, [_i]),
+    "wmdec_adaln_fused_projection": (_i, [_vp, _i, _vp, _i, _vp, _vp, _i, _i, _i, _i, _vp]),
     "decoder_default_config": (None, [ctypes.POINTER(DecoderConfig)]),
     "decoder_create": (_i, [ctypes.POINTER(DecoderConfig), ctypes.POINTER(_vp)]),
     "decoder_destroy": (_i, [_vp]),
@@ -242,6 +244,18 @@ def latent_extrapolate(z_prev, v_prev, lam, steps, z_out):
     """z_out = z_prev + steps * lam * v_prev (fp32 fused multiply-add, one rounding to z_out's type)."""
     _check(lib().wmdec_latent_extrapolate(_ptr(z_prev), _ptr(v_prev), dtype_enum(z_prev), lam, steps, _ptr(z_out),
                                           dtype_enum(z_out), z_prev.numel(), _stream()))
+
+
+def adaln_max_batch(d_cond):
+    return lib().wmdec_adaln_max_batch(d_cond)
+
+
+def adaln_fused_projection(c, w_fused, bias, out, apply_silu=True):
+    """out[b, :] = bias + w_fused @ act(c[b]); c [batch, d_cond], w_fused [rows, d_cond], out fp32 [batch, rows]."""
+    batch, d_cond = c.shape
+    rows = w_fused.shape[0]
+    _check(lib().wmdec_adaln_fused_projection(_ptr(c), dtype_enum(c), _ptr(w_fused), dtype_enum(w_fused), _ptr(bias), _ptr(out),
+                                              batch, d_cond, rows, int(apply_silu), _stream()))
 
 
 # ------------------------------------------------------------------ decoder

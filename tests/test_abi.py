@@ -165,6 +165,11 @@ def test_argument_errors_are_reported_without_a_gpu():
                                             1, 8, 8, 64, 64, None) == wmdec.ERR_INVALID_ARG       # cin2 = 0
     assert l.wmdec_gn_silu_conv3x3_shortcut(p, 2, None, None, None, None, 32, 0, p, None, 2 * p, 64, p, None, 2 * p, 2,
                                             1, 8, 8, 64, 64, None) == wmdec.ERR_INVALID_ARG       # x2 == y
+    # fused AdaLN projections
+    assert l.wmdec_adaln_max_batch(1920) == 8 and l.wmdec_adaln_max_batch(0) == 0
+    assert l.wmdec_adaln_fused_projection(p, 0, None, 1, None, p, 1, 64, 8, 1, None) == wmdec.ERR_INVALID_ARG
+    assert l.wmdec_adaln_fused_projection(p, 0, p, 1, None, 2 * p, 1, 60, 8, 1, None) == wmdec.ERR_SHAPE        # 16-byte vectors
+    assert l.wmdec_adaln_fused_projection(p, 0, p, 1, None, 2 * p, 17, 64, 8, 1, None) == wmdec.ERR_UNSUPPORTED  # batch
     # latent extrapolation
     assert l.wmdec_latent_extrapolate(p, None, 1, 0.5, 1, p, 1, 16, None) == wmdec.ERR_INVALID_ARG
     assert l.wmdec_latent_extrapolate(p, p, 1, float("nan"), 1, p, 1, 16, None) == wmdec.ERR_INVALID_ARG

@@ -437,3 +437,45 @@ def test_attention_bf16_sharp_softmax_with_the_same_storage_points():
     want = x + ref.conv2d(o, p["proj.w"], p["proj.b"])
     assert ref.rel_err(got, want) <= G.TOL[dtype]
     assert ref.rel_err(got - x, want - x) <= branch_tolerance(dtype, want, x)
+
+
+# ------------------------------------------------------------------ horizontally fused AdaLN projections (DiT)
+# d_model = d_cond = 1920 stands for the paper's 30-head transformer (64 per head; the paper gives no widths)
+@pytest.mark.parametrize("cdtype,wdtype,batch,d_cond,d_model,silu", [
+    ("f32", "bf16", 1, 1920, 1920, True),      # one frame's conditioning vector
+    ("f32", "bf16", 4, 1920, 1920, True),      # a batch of four frames
+    ("bf16", "bf16", 8, 1920, 1920, True),
+    ("f16", "f16", 3, 520, 77, False),         # ragged: d_cond not a multiple of a wavefront's 512, rows of 8 and 32
+    ("f32", "f32", 2, 12, 5, True),
+    ("f32", "bf16", 16, 1024, 40, True),       # the largest batch one launch takes
+])
+def test_adaln_fused_projection(cdtype, wdtype, batch, d_cond, d_model, silu):
+    """One launch on the row-concatenated [W_shift; W_scale; W_gate] against the oracle's three separate products."""
+    sixteen = wdtype != "f32"
+    p = synth.adaln_params(synth.weight_seed(20), d_model, d_cond, sixteen_bit=sixteen)
+    if wdtype == "f16":
+        p = {k: (G.stored(v, "f16") if k.endswith(".w") else v) for k, v in p.items()}
+    c = G.stored(rng(30).standard_normal((batch, d_cond)) * 1.5, cdtype)
+    w_fused = np.vstack([p["shift.w"], p["scale.w"], p["gate.w"]])
+    b_fused = np.concatenate([p["shift.b"], p["scale.b"], p["gate.b"]])
+    cd = torch.from_numpy(c).to(G.TORCH[cdtype]).cuda()
+    wd = torch.from_numpy(w_fused).to(G.TORCH[wdtype]).cuda()
+    out, check = G.canaried((batch, 3 * d_model), torch.float32)
+    wmdec.adaln_fused_projection(cd, wd, G.dev_f32(b_fused), out, apply_silu=silu)
+    torch.cuda.synchronize()
+    check()
+    shift, scale, gate = ref.adaln_modulation(c, p, apply_silu=silu)
+    got = out.cpu().numpy().astype(np.float64)
+    for k, want in enumerate((shift, scale, gate)):
+        err = ref.rel_err(got[:, k * d_model:(k + 1) * d_model], want)
+        assert err <= 1e-4, (k, err)          # fp32 products and sums of exactly stored operands
+
+
+def test_adaln_fused_projection_limits():
+    assert wmdec.adaln_max_batch(1920) == 8 and wmdec.adaln_max_batch(512) == 16
+    c = torch.zeros((9, 1920), dtype=torch.float32, device="cuda")
+    w = torch.zeros((24, 1920), dtype=torch.bfloat16, device="cuda")
+    out = torch.zeros((9, 24), dtype=torch.float32, device="cuda")
+    with pytest.raises(wmdec.WmdecError) as e:
+        wmdec.adaln_fused_projection(c, w, None, out)
+    assert e.value.status == wmdec.ERR_UNSUPPORTED
