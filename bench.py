@@ -114,8 +114,13 @@ def main():
     info = dec.step_info()
     reps = 10
     fam = {}
+    per_step = []
     for i, (kernel, flops, nbytes) in enumerate(info):
         ms = dec.time_step(zd, packed, out, i, reps)
+        per_step.append({"step": i, "kernel": profile_summary.short_name(kernel), "us": round(ms * 1e3, 2),
+                         "gflop": round(flops * args.batch / 1e9, 2), "mb": round(nbytes * args.batch / 1e6, 2),
+                         "tflops": round(flops * args.batch / (ms * 1e-3) / 1e12, 1) if ms > 0 else None,
+                         "gbps": round(nbytes * args.batch / (ms * 1e-3) / 1e9, 1) if ms > 0 else None})
         f = fam.setdefault(kernel, {"ms": 0.0, "flops": 0.0, "bytes": 0.0, "launches": 0})
         f["ms"] += ms
         f["flops"] += flops * args.batch
@@ -182,7 +187,7 @@ def main():
                                             if args.separate_merge else "from the producer's epilogue, no merge launch"),
                              "shortcut": "separate launch" if args.separate_shortcut else "folded into conv2"}},
         "tflops": round(dec.flops_per_frame() * fps / 1e12, 1),
-        "roofline": roofline, "cpu_baseline": cpu, "kernel_families": families}))
+        "roofline": roofline, "cpu_baseline": cpu, "kernel_families": families, "graph_steps": per_step}))
 
 
 if __name__ == "__main__":

@@ -32,9 +32,9 @@ extern "C" {
  * step `step` `reps` times back to back between two HIP events on `stream`,
  * waits, and returns the mean milliseconds per launch.  The step runs on what
  * the workspace holds; steps timed in plan order see the tensors of a real
- * run, except that the second convolution of a channel-changing ResBlock
- * accumulates onto its shortcut in place, once per repetition.  The timing
- * does not depend on the values; call decoder_run again before using the
+ * run, except that with separate_shortcut set the second convolution of a
+ * channel-changing ResBlock accumulates onto its shortcut in place, once per
+ * repetition.  Kernels branch on no tensor value; call decoder_run again before using the
  * frame or the workspace tensors. */
 int decoder_set_profiling(wmdec_decoder* dec, int enable);
 int decoder_num_steps(const wmdec_decoder* dec);

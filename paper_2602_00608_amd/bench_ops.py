@@ -84,7 +84,7 @@ def main():
 
     def line(name, shape, us, work, unit, peak):
         warm, cold = us
-        print("%-20s %-22s warm %8.1f us %8.1f %s (%4.1f%%)   cold %8.1f us %8.1f %s (%4.1f%% of %.0f)"
+        print("%-30s %-22s warm %8.1f us %8.1f %s (%4.1f%%)   cold %8.1f us %8.1f %s (%4.1f%% of %.0f)"
               % (name, shape, warm, work / warm / 1e6 if unit == "TFLOP/s" else work / warm / 1e3, unit,
                  (work / warm / 1e6 if unit == "TFLOP/s" else work / warm / 1e3) / peak * 100,
                  cold, work / cold / 1e6 if unit == "TFLOP/s" else work / cold / 1e3, unit,
@@ -141,6 +141,20 @@ def main():
     us = timeit(lambda: wmdec.upsample2x_nearest(x, y), args.reps)
     line("upsample2x_nearest", "%4d       @%3dx%3d" % (256, 240, 360), us, (x.numel() + y.numel()) * 2, "GB/s", PEAK_GBPS)
 
+
+    # how much of the matrix-core rate is a matter of operand values: the same plain 3x3 convolution (no normalisation,
+    # no residual: identical instruction stream and memory traffic) on N(0,1) activations and on zeros
+    for cin, cout, h, w in [(256, 256, 240, 360), (512, 512, 120, 180)]:
+        y = torch.empty((1, h, w, cout), device="cuda", dtype=dt)
+        wsrc = torch.randn((cout, cin, 3, 3), device="cuda") / (cin * 9) ** 0.5
+        bias = 0.01 * torch.randn(cout, device="cuda")
+        wp = torch.empty(wmdec.conv_packed_bytes(cout, cin, 3, en), dtype=torch.uint8, device="cuda")
+        wmdec.pack_conv_weights(wsrc, wp, en)
+        flops = 2.0 * 9 * cin * cout * h * w
+        for label, x in (("N(0,1) input", torch.randn((1, h, w, cin), device="cuda").to(dt)),
+                         ("all-zero input", torch.zeros((1, h, w, cin), device="cuda", dtype=dt))):
+            us = timeit(lambda: wmdec.gn_silu_conv3x3(x, None, None, None, None, groups, False, wp, bias, None, y), args.reps)
+            line("plain conv3x3, " + label, "%4d->%4d @%3dx%3d" % (cin, cout, h, w), us, flops, "TFLOP/s", PEAK_TFLOPS)
 
     # horizontally fused AdaLN projections: one launch on [W_shift; W_scale; W_gate] against three launches
     d = 1920
