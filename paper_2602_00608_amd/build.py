@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libwmdec.so")
 
-SOURCES = ["api.cpp", "kernels_gn.hip", "kernels_conv_direct.hip", "kernels_conv_mfma.hip",
+SOURCES = ["api.cpp", "kernels_gn.hip", "kernels_conv_direct.hip", "kernels_conv_mfma.hip", "kernels_conv_taps.hip",
            "kernels_misc.hip", "kernels_attn.hip", "kernels_adaln.hip"]
 
 FLAGS = ["-x", "hip", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

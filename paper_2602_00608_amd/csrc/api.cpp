@@ -28,6 +28,7 @@ int hip_fail(hipError_t e, const char* what) {
 }
 
 int launch_conv(const ConvArgs& a, hipStream_t s) {
+  if (conv_taps_supported(a)) return launch_conv_taps(a, s);
   if (conv_mfma_supported(a)) return launch_conv_mfma(a, s);
   WMDEC_REQUIRE(!a.x2, WMDEC_ERR_UNSUPPORTED, "conv: only the matrix-core kernel folds a shortcut into the contraction");
   if (conv_small_cin_supported(a)) return launch_conv_small_cin(a, s);
@@ -35,6 +36,7 @@ int launch_conv(const ConvArgs& a, hipStream_t s) {
 }
 
 const char* conv_kernel_label(const ConvArgs& a) {
+  if (conv_taps_supported(a)) return conv_taps_label(a);
   if (!conv_mfma_supported(a)) return conv_small_cin_supported(a) ? "conv_small_cin_kernel" : "conv_direct_kernel";
   return conv_mfma_label(a);
 }
@@ -83,6 +85,7 @@ struct Step {
   int emit_stats = 0;      // CONV: its epilogue also writes the GroupNorm moments of its output
   int from_producer = 0;   // STATS: only merge the moments the producing convolution left behind
   int emit_rows = -1;      // CONV (with emit_stats): also leaves row moments in row buffer 0 / 1; no merge launch follows
+  int emit_direct = 0;     //   ... as the triples of its workgroups themselves (few spatial tiles), without a merge by row
   int rows_from = -1;      // CONV with norm: takes the statistics of its input from row buffer 0 / 1 ...
   int rows_count = 0;      //   ... which holds this many rows per (sample, group)
   size_t w_off = 0, b_off = 0, gamma_off = 0, beta_off = 0;
@@ -258,9 +261,22 @@ static void fuse_stats_into_producers(wmdec_decoder& d) {
     if (d.cfg.separate_merge_launch || i + 1 >= d.steps.size()) continue;
     Step& cons = d.steps[i + 1];
     if (cons.kind != Step::CONV || !cons.norm || cons.src != st.src || !conv_mfma_supported(step_shape_args(d, cons, 1))) continue;
+    if (conv_taps_supported(step_shape_args(d, cons, 1))) continue;   // that kernel takes mean / rstd only
+    // A producer with few spatial tiles needs no merge of its own at all: the consumer reads its triples as they are.
+    const int slots = conv_mfma_stats_slots(step_shape_args(d, d.steps[j], 1));
+    if (slots <= 128) {
+      d.steps[j].emit_rows = parity;
+      d.steps[j].emit_direct = 1;
+      cons.rows_from = parity;
+      cons.rows_count = slots;
+      parity ^= 1;
+      st.kind = Step::NONE;
+      d.launches -= 1;
+      continue;
+    }
     int rows = 0, ctiles = 0, per_row = 0;
     conv_mfma_row_extents(step_shape_args(d, d.steps[j], 1), &rows, &ctiles, &per_row);
-    if (rows > 64) continue;   // the consumer's prologue merges at most 64 rows
+    if (rows > 64) continue;   // keeps the consumer's merge short
     // The hand-over keeps every workgroup of the producer resident for two more memory round trips (its stores, its
     // ticket).  Measured, that costs a launch of several rounds of workgroups as much as the merge launch it saves;
     // it wins where the producer is a single round (at most three workgroups per compute unit, per sample).
@@ -385,7 +401,8 @@ static WsLayout ws_layout(const wmdec_decoder* d, int batch) {
   for (const Step& st : d->steps) {
     if (st.kind != Step::CONV || st.emit_rows < 0) continue;
     int rows = 0, ctiles = 0, per_row = 0;
-    conv_mfma_row_extents(step_shape_args(*d, st, 1), &rows, &ctiles, &per_row);
+    if (st.emit_direct) { rows = conv_mfma_stats_slots(step_shape_args(*d, st, 1)); ctiles = 0; }
+    else conv_mfma_row_extents(step_shape_args(*d, st, 1), &rows, &ctiles, &per_row);
     if ((size_t)rows * ctiles > max_tickets) max_tickets = (size_t)rows * ctiles;
     if ((size_t)rows > max_rows) max_rows = rows;
   }
@@ -875,8 +892,8 @@ static int launch_step(wmdec_decoder* dec, const WsLayout& L, const Step& st, co
         if (st.emit_stats) {
           a.stats_groups = c.groups;
           (*emitted_slots) = conv_mfma_stats_slots(a);
-          if ((*emitted_slots) > 0) a.stats_ws = ws + L.stats_ws;
-          if (st.emit_rows >= 0) { a.rows_out = ws + L.rows[st.emit_rows]; a.tickets = ws + L.conv_tickets; }
+          if ((*emitted_slots) > 0) a.stats_ws = st.emit_direct ? ws + L.rows[st.emit_rows] : ws + L.stats_ws;
+          if (st.emit_rows >= 0 && !st.emit_direct) { a.rows_out = ws + L.rows[st.emit_rows]; a.tickets = ws + L.conv_tickets; }
         }
         rc = launch_conv(a, s);
         break;

@@ -120,6 +120,11 @@ bool conv_mfma_uses_phase(const ConvArgs& a);
 int conv_mfma_stats_slots(const ConvArgs& a);
 void conv_mfma_row_extents(const ConvArgs& a, int* tile_rows, int* channel_tiles, int* tiles_per_row);
 const char* conv_mfma_label(const ConvArgs& a);   // instantiation name, valid until the thread's next call
+// kernels_conv_taps.hip: 3x3 convolution with at most three output channels into a planar fp32 tensor (the frame),
+// evaluated as a 1x1 contraction onto (tap, channel) pairs followed by nine shifted adds
+bool conv_taps_supported(const ConvArgs& a);
+int launch_conv_taps(const ConvArgs& a, hipStream_t s);
+const char* conv_taps_label(const ConvArgs& a);
 // picks the kernel
 int launch_conv(const ConvArgs& a, hipStream_t s);
 const char* conv_kernel_label(const ConvArgs& a);

@@ -331,8 +331,12 @@ constexpr int tile_row_elems(int tw, int pad, int kc) {
 }
 constexpr int tile_buf_elems(int th, int tw, int pad, int kc) { return (th + 2 * pad) * tile_row_elems(tw, pad, kc) + (kc + 8); }
 
-template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC, int ACT, bool PH = false>
-__global__ __launch_bounds__(64 * WM * WN, resident_workgroups(wave_m_tiles(TH, TW, WM, PH) * NI, WM, WN))
+// RING: 0 = weight-fragment ring sized by prefetch_ring; otherwise its length in k-steps (a divisor of the k-steps of
+// a chunk).  The whole-chunk ring is for launches that leave a compute unit at most two workgroups: there a wavefront
+// is alone on its SIMD, nothing else hides the latency of weights that come from beyond the L2 (every layer's weights
+// are new to the L2 inside a decoder run), and the registers of the third workgroup are free for it.
+template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC, int ACT, bool PH = false, int RING = 0>
+__global__ __launch_bounds__(64 * WM * WN, RING > 6 ? 2 : resident_workgroups(wave_m_tiles(TH, TW, WM, PH) * NI, WM, WN))
 void conv_mfma_kernel(MfmaParams p) {
   static_assert(WM * WN == 4 || WM * WN == 8, "four or eight wavefronts");
   constexpr int NT = 64 * WM * WN;               // threads of the workgroup
@@ -395,7 +399,7 @@ void conv_mfma_kernel(MfmaParams p) {
     a_off[mi] = ty * ROW + tx * PS + 8 * lk + (PH ? (wave >> 1) * ROW + (wave & 1) * PS : 0);
   }
   constexpr int KK = KC / 16;
-  constexpr int D = prefetch_ring(KT * KT * KK, MI * NI);   // weight fragments are fetched D-1 k-steps ahead
+  constexpr int D = RING > 0 ? RING : prefetch_ring(KT * KT * KK, MI * NI);   // weight fragments are fetched D-1 k-steps ahead
   static_assert((KT * KT * KK) % D == 0, "the ring position must be the same at every chunk start");
   const int tap_stride = p.cin_blocks * p.cout_blocks * 1024, kk_stride = p.cout_blocks * 1024;   // bytes
   // byte offset of this wavefront's fragment column (wave-uniform; the lane's 16 bytes are added by the load)
@@ -543,24 +547,45 @@ void conv_mfma_kernel(MfmaParams p) {
       // mean / rstd of every group from the row triples its producer left: eight lanes per group take the rows
       // round-robin in order, then a fixed butterfly; (mean, rstd) parked behind the table
       float2* s_stat = s_ab + p.cin;
+      // Launches that leave a wavefront alone on its SIMD (RING): gamma / beta of this thread's first two table
+      // entries are requested together with the triples, one memory round trip less in front of the first chunk
+      // (elsewhere other workgroups cover that latency and the registers are better left to the main loop).
+      constexpr int PRE = RING > 6 ? 2 : 0;
+      float gpre[2] = {0.f, 0.f}, bpre[2] = {0.f, 0.f};
+#pragma unroll
+      for (int j = 0; j < PRE; ++j) {
+        const int c = min(tid + j * NT, p.cin - 1);
+        gpre[j] = p.gamma[c]; bpre[j] = p.beta[c];
+      }
       const int sub = tid & 7;
       for (int g = tid >> 3; g < p.groups; g += NT / 8) {
         const Moments* row = p.rows_in + (size_t)(n * p.groups + g) * p.rows_in_count;
-        Moments t[8];       // at most 64 rows (checked on the host): all loads in flight before the first merge
+        Moments m{0.f, 0.f, 0.f};
+        for (int r0 = sub; r0 < p.rows_in_count; r0 += 64) {   // eight loads in flight per lane before the first merge
+          Moments t[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-          const int r = sub + 8 * k;
-          t[k] = row[min(r, p.rows_in_count - 1)];
-          if (r >= p.rows_in_count) t[k].n = 0.f;
+          for (int k = 0; k < 8; ++k) {
+            const int r = r0 + 8 * k;
+            t[k] = row[min(r, p.rows_in_count - 1)];
+            if (r >= p.rows_in_count) t[k].n = 0.f;
+          }
+#pragma unroll
+          for (int k = 0; k < 8; ++k) m = merge(m, t[k]);
         }
-        Moments m = t[0];
-#pragma unroll
-        for (int k = 1; k < 8; ++k) m = merge(m, t[k]);
         for (int mask = 1; mask < 8; mask <<= 1) m = butterfly(m, lane, mask);
         if (sub == 0) s_stat[g] = make_float2(m.mean, 1.0f / sqrtf(m.m2 / m.n + p.eps));
       }
       __syncthreads();
-      for (int c = tid; c < p.cin; c += NT) {
+#pragma unroll
+      for (int j = 0; j < PRE; ++j) {
+        const int c = tid + j * NT;
+        if (c < p.cin) {
+          const float2 st = s_stat[c / cpg];
+          const float a = gpre[j] * st.y;
+          s_ab[c] = make_float2(k * a, k * (bpre[j] - st.x * a));
+        }
+      }
+      for (int c = tid + PRE * NT; c < p.cin; c += NT) {
         const float2 st = s_stat[c / cpg];
         const float a = p.gamma[c] * st.y;
         s_ab[c] = make_float2(k * a, k * (p.beta[c] - st.x * a));
@@ -667,7 +692,7 @@ void conv_mfma_kernel(MfmaParams p) {
   }
 }
 
-template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC, bool PH = false>
+template <typename T, typename TO, int TH, int TW, int WM, int WN, int NI, int KS, int KC, bool PH = false, int RING = 0>
 int launch_cfg(const ConvArgs& a, hipStream_t s) {
   constexpr int PAD = PH ? 1 : KS / 2;
   constexpr int TN = WN * NI * 32;
@@ -687,7 +712,7 @@ int launch_cfg(const ConvArgs& a, hipStream_t s) {
   p.rows_out = (Moments*)a.rows_out; p.tickets = (unsigned*)a.tickets;
   p.rows_in = (const Moments*)a.rows_in; p.rows_in_count = a.rows_in_count; p.eps = a.eps;
   WMDEC_REQUIRE(!p.rows_out || (p.stats && p.tickets), WMDEC_ERR_INVALID_ARG, "conv_mfma: row moments need the triple scratch and the ticket counters");
-  WMDEC_REQUIRE(!p.rows_in || (p.rows_in_count >= 1 && p.rows_in_count <= 64), WMDEC_ERR_UNSUPPORTED, "conv_mfma: at most 64 rows of moments can be merged in the prologue");
+  WMDEC_REQUIRE(!p.rows_in || (p.rows_in_count >= 1 && p.rows_in_count <= 128), WMDEC_ERR_UNSUPPORTED, "conv_mfma: at most 128 triples per group can be merged in the prologue");
   p.norm = a.mean != nullptr || a.rows_in != nullptr;
   p.x2 = nullptr; p.w2 = nullptr; p.bias2 = nullptr; p.cin2 = 0; p.w2_bytes = 0;
   if (a.x2) {
@@ -701,9 +726,9 @@ int launch_cfg(const ConvArgs& a, hipStream_t s) {
   const size_t patch = (size_t)(WM * WN) * patch_floats(NI) * sizeof(float);   // epilogue patches of the wavefronts
   if (smem < patch) smem = patch;
   WMDEC_REQUIRE(smem <= 80 * 1024, WMDEC_ERR_UNSUPPORTED, "conv_mfma: %zu bytes of LDS needed", smem);
-  void (*kern)(MfmaParams) = !p.norm ? conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 0, PH>
-                             : (a.silu ? conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 2, PH>
-                                       : conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 1, PH>);
+  void (*kern)(MfmaParams) = !p.norm ? conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 0, PH, RING>
+                             : (a.silu ? conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 2, PH, RING>
+                                       : conv_mfma_kernel<T, TO, TH, TW, WM, WN, NI, KS, KC, 1, PH, RING>);
   // once per instantiation and activation mode (80 KiB: two workgroups per compute unit)
   static std::once_flag attr_once[3];
   hipError_t attr_err = hipSuccess;
@@ -753,12 +778,21 @@ TileId pick_tile(const ConvArgs& a) {
   return n128 ? T128x128_ROW : T128x64_ROW;
 }
 
+// The 128x128 tile with a whole chunk of weight fragments in flight (see RING): launches of at most two workgroups per
+// compute unit.  Unlike the tile shape this may depend on the batch: the ring changes no summation order.
+bool whole_chunk_ring(const ConvArgs& a) {
+  if (pick_tile(a) != T128x128_1x4) return false;
+  const long wgs = (long)((a.h + 7) / 8) * ((a.w + 15) / 16) * (a.cout / 128) * a.n;
+  return wgs <= 2 * 256;
+}
+
 template <typename T, typename TO>
 int launch_3x3(const ConvArgs& a, hipStream_t s) {
   switch (pick_tile(a)) {
     case T128x64: return launch_cfg<T, TO, 8, 16, 4, 1, 2, 3, 32>(a, s);
     case T_PHASE: return launch_cfg<T, TO, 8, 16, 4, 1, 2, 3, 32, true>(a, s);
-    case T128x128_1x4: return launch_cfg<T, TO, 8, 16, 1, 4, 1, 3, 32>(a, s);
+    case T128x128_1x4:
+      return whole_chunk_ring(a) ? launch_cfg<T, TO, 8, 16, 1, 4, 1, 3, 32, false, 18>(a, s) : launch_cfg<T, TO, 8, 16, 1, 4, 1, 3, 32>(a, s);
     case T128x256: return launch_cfg<T, TO, 8, 16, 1, 4, 2, 3, 32>(a, s);
     default: return launch_cfg<T, TO, 8, 32, 4, 1, 1, 3, 32>(a, s);
   }
@@ -835,8 +869,9 @@ const char* conv_mfma_label(const ConvArgs& a) {
   const TileShape& ts = kTiles[t];
   const char* ty = a.op_dtype == WMDEC_BF16 ? "wmdec::bf16_t" : "wmdec::f16_t";
   const int act = a.mean == nullptr && a.rows_in == nullptr && !a.groups_norm ? 0 : (a.silu ? 2 : 1);
-  snprintf(buf, sizeof(buf), "conv_mfma_kernel<%s, %s, %d, %d, %d, %d, %d, %d, %d, %d, %s>", ty,
-           a.y_dtype == WMDEC_F32 ? "float" : ty, ts.th, ts.tw, ts.wm, ts.wn, ts.ni, a.ksize, kc, act, t == T_PHASE ? "true" : "false");
+  snprintf(buf, sizeof(buf), "conv_mfma_kernel<%s, %s, %d, %d, %d, %d, %d, %d, %d, %d, %s, %d>", ty,
+           a.y_dtype == WMDEC_F32 ? "float" : ty, ts.th, ts.tw, ts.wm, ts.wn, ts.ni, a.ksize, kc, act, t == T_PHASE ? "true" : "false",
+           a.ksize == 3 && whole_chunk_ring(a) ? 18 : 0);
   return buf;
 }
 

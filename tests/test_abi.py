@@ -97,8 +97,12 @@ def test_step_accounting_adds_up():
     assert all(k for k, _, _ in info)
     convs = [(k, f, b) for k, f, b in info if k.startswith("conv_mfma_kernel<")]
     # 30 ResBlock convolutions (the two 1x1 shortcuts are folded into their second convolutions), three upsampling
-    # convolutions, qkv and output projection, conv_out: 36 - 2 launches on the matrix cores
-    assert len(convs) == 34 and all(k.endswith(">") for k, _, _ in convs)
+    # convolutions, qkv and output projection: 33 launches of the implicit-GEMM kernel; conv_out (three output
+    # channels) runs as a contraction onto (tap, channel) pairs
+    assert len(convs) == 33 and all(k.endswith(">") for k, _, _ in convs)
+    assert info[-1][0] == "conv_taps_kernel<wmdec::f16_t, 8, 2>"
+    # the ten 512 -> 512 layers at 60x90 leave compute units at most one workgroup: whole-chunk weight ring
+    assert sum(1 for k, _, _ in convs if k.endswith(", 18>")) == 10
     # the second convolution of the 512 -> 256 block carries its shortcut: K = 9*256 + 512, and reads the block input
     fold_flops = 2.0 * (9 * 256 + 512) * 256 * 240 * 360
     fold_bytes = (2 * 240 * 360 * 256 + 240 * 360 * 512) * 2 + (9 * 256 * 256 + 512 * 256) * 2
@@ -109,8 +113,9 @@ def test_step_accounting_adds_up():
     assert any(f == want_flops and b == want_bytes for _, f, b in convs)
     # 30 normalisations: conv_in's output takes the streaming statistics pass; every other one gets its moments from
     # the epilogue of the convolution that produced its input.  Where that producer is a single round of workgroups
-    # (the 60x90 and 120x180 layers: 21 normalisations) its last workgroup per tile row and the consumer's prologue do
-    # the merge; the 8 producers of several rounds (240x360, 480x720) keep a small merge launch.
+    # (the 60x90 and 120x180 layers: 21 normalisations) the consumer's prologue merges either the producer's triples
+    # themselves (few tiles) or what its last workgroup per tile row merged; the 8 producers of several rounds (240x360,
+    # 480x720) keep a small merge launch.
     assert sum(1 for k, _, _ in info if k == "gn_stats_vec") == 1 and sum(1 for k, _, _ in info if k == "gn_finalize") == 8
     cfg = wmdec.decoder_default_config()
     cfg.separate_merge_launch = 1

@@ -232,6 +232,33 @@ def test_decoder_reduced_size(dtype):
     assert np.array_equal(one[0], got[1])
 
 
+@pytest.mark.parametrize("dtype,last", [("f16", 128), ("bf16", 128), ("f16", 64)])
+def test_last_convolution_as_taps_contraction(dtype, last):
+    """The decoder's last layer (few output channels, planar fp32 frame) runs as a 1x1 contraction onto (tap, channel)
+    pairs followed by nine shifted adds.  Reduced decoder whose last level has the full decoder's 128 (or 64) channels,
+    frame 40x56: a ragged tile column (56 = 32 + 24), image borders in every tile, batch 2, random affine."""
+    cfg = small_cfg(G.ENUM[dtype])
+    cfg.latent_h, cfg.latent_w = 5, 7
+    chans = (512, 128, 64, last)
+    cfg.level_channels[3] = last
+    dec = wmdec.Decoder(cfg)
+    assert dec.step_info()[-1][0].startswith("conv_taps_kernel<"), dec.step_info()[-1][0]
+    dec.close()
+    spec = synth.decoder_weight_spec(level_channels=chans, resblocks_per_level=2)
+    weights = synth.draw_params(spec, synth.weight_seed(13), random_affine=True)
+    z = synth.latent_sequence(workload=13, frames=2, h=5, w=7)
+    got = run_decoder(cfg, weights, z)
+    want = ref.decoder(z, weights, level_channels=chans, resblocks_per_level=2, groups=32, eps=1e-6)
+    assert got.shape == want.shape == (2, 3, 40, 56)
+    err = ref.rel_err(got, want)
+    print(dtype, last, float("%.3g" % err))
+    assert err <= (G.TOL["f16"] if dtype == "f16" else 8e-2), err
+    # the borders of the frame (zero padding in the activated domain) and the ragged column, on their own
+    for sl in (np.s_[:, :, 0, :], np.s_[:, :, -1, :], np.s_[:, :, :, 0], np.s_[:, :, :, -1], np.s_[:, :, :, 32:]):
+        e = np.abs(got[sl] - want[sl]).max() / np.sqrt((want ** 2).mean())
+        assert e <= (G.TOL["f16"] if dtype == "f16" else 8e-2), (sl, e)
+
+
 @pytest.fixture(scope="module")
 def workload4():
     weights = synth.decoder_weights(4)
