@@ -411,7 +411,7 @@ static WsLayout ws_layout(const wmdec_decoder* d, int batch) {
   for (int i = 0; i < 2; ++i) { L.rows[i] = o; o += align_up(max_rows * d->cfg.max_batch * d->cfg.groups * 3 * sizeof(float), 256); }
   for (int i = 0; i < 3; ++i) { L.act[i] = o; o += act; }
   L.qkv = o; o += align_up((size_t)batch * d->attn_t * 3 * d->attn_c * es, 256);
-  L.vt = o; o += align_up((size_t)batch * d->attn_c * d->attn_tpad * es, 256);
+  L.vt = o; o += align_up((size_t)batch * flash_attention_vt_elems(d->attn_t, d->attn_c) * es, 256);
   L.attn_o = o; o += align_up((size_t)batch * d->attn_t * d->attn_c * es, 256);
   L.attn_scratch = o; o += align_up(flash_attention_scratch_bytes(batch, d->attn_t, d->attn_c), 256);
   L.mean = o; o += align_up((size_t)batch * d->cfg.groups * sizeof(float), 256);
@@ -648,10 +648,9 @@ int wmdec_nhwc_to_nchw(const void* src, int sd, void* dst, int dd, int n, int c,
 
 // ---- attention
 static void attn_ws_layout(int n, int t, int c, size_t es, size_t* qkv, size_t* vt, size_t* o, size_t* scratch, size_t* total) {
-  const int tpad = (t + 31) / 32 * 32;
   size_t off = 0;
   *qkv = off; off += align_up((size_t)n * t * 3 * c * es, 256);
-  *vt = off; off += align_up((size_t)n * c * tpad * es, 256);
+  *vt = off; off += align_up((size_t)n * flash_attention_vt_elems(t, c) * es, 256);
   *o = off; off += align_up((size_t)n * t * c * es, 256);
   *scratch = off; off += align_up(flash_attention_scratch_bytes(n, t, c), 256);
   *total = off;
@@ -678,7 +677,7 @@ static int attention_impl(const void* x, int act_dtype, const float* mean, const
   if (rc != WMDEC_OK) return rc;
   // V^T[n][d][key]: transpose the v columns of the qkv buffer
   rc = launch_transpose((const char*)qkv + (size_t)2 * c * es, act_dtype, vt, act_dtype, n, t, c, (size_t)3 * c,
-                        (size_t)t * 3 * c, (size_t)tpad, (size_t)c * tpad, s);
+                        (size_t)t * 3 * c, 0 /* blocks of 32 keys */, flash_attention_vt_elems(t, c), s);
   if (rc != WMDEC_OK) return rc;
   rc = launch_flash_attention(qkv, (const char*)qkv + (size_t)c * es, (size_t)3 * c, (size_t)t * 3 * c, vt, tpad, ob,
                               scratch, act_dtype, n, t, c, 1.0f / sqrtf((float)c), s);
@@ -902,7 +901,7 @@ static int launch_step(wmdec_decoder* dec, const WsLayout& L, const Step& st, co
         const size_t es = dtype_size(c.act_dtype);
         const int t = st.h * st.w;
         rc = launch_transpose(ws + L.qkv + (size_t)2 * st.cin * es, c.act_dtype, ws + L.vt, c.act_dtype, batch, t, st.cin,
-                              (size_t)3 * st.cin, (size_t)t * 3 * st.cin, (size_t)dec->attn_tpad, (size_t)st.cin * dec->attn_tpad, s);
+                              (size_t)3 * st.cin, (size_t)t * 3 * st.cin, 0 /* blocks of 32 keys */, flash_attention_vt_elems(t, st.cin), s);
         break;
       }
       case Step::NONE: break;

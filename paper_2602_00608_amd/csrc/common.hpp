@@ -168,9 +168,11 @@ int launch_adaln_projection(const void* c, int c_dtype, const void* w, int w_dty
                             int d_cond, int rows, int apply_silu, hipStream_t s);
 
 // kernels_attn.hip
-// q,k: [n][t][ld] rows of d elements (16-bit type), vt: [n][d][t_pad] keys contiguous, o: [n][t][d]
+// q,k: [n][t][ld] rows of d elements (16-bit type), vt: [n][t_pad / 32][d][40] (V transposed in blocks of 32 keys, rows padded to 40 elements, keys past t zero), o: [n][t][d]
 // scratch: flash_attention_scratch_bytes(n, t, d) bytes (partial outputs of the key splits), may be null if 0
 size_t flash_attention_scratch_bytes(int n, int t, int d);
+// elements of V^T per sample in the blocked, row-padded layout the kernel reads (see launch_transpose with dst_ld = 0)
+size_t flash_attention_vt_elems(int t, int d);
 int launch_flash_attention(const void* q, const void* k, size_t qk_ld, size_t qk_batch_stride,
                            const void* vt, int t_pad, void* o, void* scratch, int dtype, int n, int t, int d,
                            float scale, hipStream_t s);

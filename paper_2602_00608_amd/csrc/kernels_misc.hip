@@ -86,8 +86,11 @@ __global__ __launch_bounds__(256) void pack_upconv_phase_kernel(const S* __restr
   dst[i] = from_float<D>(acc);
 }
 
-// dst[b][i][j] = src[b][j][i], 32x32 tiles through LDS
-template <typename S, typename D>
+// dst[b][i][j] = src[b][j][i], 32x32 tiles through LDS.  BLOCKED (dst_ld = 0): the destination is cut into blocks of 32
+// source rows, dst[b][j / 32][i][40] with j % 32 in the first 32 of a row's 40 elements and zeros for source rows past
+// the end: the image of the attention kernel's V^T tile in LDS (32 keys, rows padded to 40 elements), which that
+// kernel copies as one contiguous run.
+template <typename S, typename D, bool BLOCKED = false>
 __global__ __launch_bounds__(256) void transpose_kernel(const S* __restrict__ src, D* __restrict__ dst, int rows, int cols,
                                                         size_t src_ld, size_t src_bs, size_t dst_ld, size_t dst_bs) {
   __shared__ float tile[32][33];
@@ -101,7 +104,11 @@ __global__ __launch_bounds__(256) void transpose_kernel(const S* __restrict__ sr
   __syncthreads();
   for (int k = ty; k < 32; k += 8) {
     const int c = c0 + k, r = r0 + tx;
-    if (r < rows && c < cols) dst[(size_t)b * dst_bs + (size_t)c * dst_ld + r] = from_float<D>(tile[tx][k]);
+    if (BLOCKED) {
+      if (c < cols) dst[(size_t)b * dst_bs + ((size_t)blockIdx.y * cols + c) * 40 + tx] = from_float<D>(r < rows ? tile[tx][k] : 0.f);
+    } else if (r < rows && c < cols) {
+      dst[(size_t)b * dst_bs + (size_t)c * dst_ld + r] = from_float<D>(tile[tx][k]);
+    }
   }
 }
 
@@ -151,7 +158,8 @@ int pack_phase_t(const void* src, void* dst, int cout, int cin, hipStream_t s) {
 template <typename S, typename D>
 int transpose_t(const void* src, void* dst, int batch, int rows, int cols, size_t sld, size_t sbs, size_t dld, size_t dbs, hipStream_t s) {
   dim3 grid((unsigned)((cols + 31) / 32), (unsigned)((rows + 31) / 32), (unsigned)batch);
-  hipLaunchKernelGGL((transpose_kernel<S, D>), grid, dim3(256), 0, s, (const S*)src, (D*)dst, rows, cols, sld, sbs, dld, dbs);
+  if (dld == 0) hipLaunchKernelGGL((transpose_kernel<S, D, true>), grid, dim3(256), 0, s, (const S*)src, (D*)dst, rows, cols, sld, sbs, dld, dbs);
+  else hipLaunchKernelGGL((transpose_kernel<S, D>), grid, dim3(256), 0, s, (const S*)src, (D*)dst, rows, cols, sld, sbs, dld, dbs);
   WMDEC_HIP(hipGetLastError());
   return WMDEC_OK;
 }
