@@ -142,6 +142,25 @@ def main():
     line("upsample2x_nearest", "%4d       @%3dx%3d" % (256, 240, 360), us, (x.numel() + y.numel()) * 2, "GB/s", PEAK_GBPS)
 
 
+    # mid-block attention as one call (qkv projection, V transpose, attention core + combine, output projection with
+    # the residual): 5400 tokens, one head of 512
+    c, h, w = 512, 60, 90
+    x = torch.randn((1, h, w, c), device="cuda").to(dt)
+    y = torch.empty_like(x)
+    mean, rstd, _ = stats_of(x)
+    gamma, beta = torch.ones(c, device="cuda"), torch.zeros(c, device="cuda")
+    wq = torch.randn((3 * c, c, 1, 1), device="cuda") / c ** 0.5
+    wo = torch.randn((c, c, 1, 1), device="cuda") / c ** 0.5
+    bq, bo = 0.01 * torch.randn(3 * c, device="cuda"), 0.01 * torch.randn(c, device="cuda")
+    wqp = torch.empty(wmdec.conv_packed_bytes(3 * c, c, 1, en), dtype=torch.uint8, device="cuda")
+    wop = torch.empty(wmdec.conv_packed_bytes(c, c, 1, en), dtype=torch.uint8, device="cuda")
+    wmdec.pack_conv_weights(wq, wqp, en)
+    wmdec.pack_conv_weights(wo, wop, en)
+    aws = torch.empty(wmdec.attention_workspace_bytes(1, h, w, c), dtype=torch.uint8, device="cuda")
+    us = timeit(lambda: wmdec.attention(x, mean, rstd, gamma, beta, groups, wqp, bq, wop, bo, y, aws), args.reps)
+    t = h * w
+    line("attention block (5 launches)", "%4d       @%3dx%3d" % (c, h, w), us, 4.0 * t * t * c + 2.0 * t * c * 4 * c, "TFLOP/s", PEAK_TFLOPS)
+
     # how much of the matrix-core rate is a matter of operand values: the same plain 3x3 convolution (no normalisation,
     # no residual: identical instruction stream and memory traffic) on N(0,1) activations and on zeros
     for cin, cout, h, w in [(256, 256, 240, 360), (512, 512, 120, 180)]:

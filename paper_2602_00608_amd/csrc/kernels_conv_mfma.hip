@@ -256,14 +256,21 @@ __device__ __forceinline__ u32x4 load_fragment(__amdgpu_buffer_rsrc_t rsrc, int 
 // and each k-step pays a full memory latency.
 // VALU_PER_MFMA: -1 pins the order as written (slot hook after the MFMAs of an M tile); >= 0 asks the scheduler to
 // interleave that many vector-ALU instructions behind every MFMA of a k-step.
-template <typename T, int MI, int NI, int KS, int KC, int ROW, int PS, int D, bool SLICED, int VALU_PER_MFMA, typename Slice>
+// AD: how many k-steps ahead the A fragments are read (1 or 2).  One step is MI - 1 MFMAs of slack, about the LDS
+// latency: enough where other wavefronts of the SIMD fill the gaps, too little for a wavefront that is alone on it.
+template <typename T, int MI, int NI, int KS, int KC, int ROW, int PS, int D, bool SLICED, int VALU_PER_MFMA, typename Slice, int AD = 1>
 __device__ __forceinline__ void mfma_chunk(const T* buf, const int (&a_off)[MI], __amdgpu_buffer_rsrc_t wrsrc, int bcur, int bnext,
                                            int tap_stride, int kk_stride, int lane16, u32x4 (&bq)[D][NI],
                                            f32x16 (&acc)[MI][NI], Slice&& slice) {
   constexpr int KK = KC / 16, STEPS = KS * KS * KK;
-  u32x4 af[MI];
+  static_assert(AD == 1 || AD == 2, "A fragments one or two k-steps ahead");
+  u32x4 af[AD][MI];   // af[s % AD]: fragments of k-step s
 #pragma unroll
-  for (int mi = 0; mi < MI; ++mi) af[mi] = *reinterpret_cast<const u32x4*>(buf + a_off[mi]);
+  for (int a = 0; a < AD && a < STEPS; ++a) {
+    const int tap = a / KK, kk = a % KK;
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) af[a][mi] = *reinterpret_cast<const u32x4*>(buf + a_off[mi] + (tap / KS) * ROW + (tap % KS) * PS + kk * 16);
+  }
   // one k-step; the slot hook runs after the MFMAs of every M tile so that its vector-ALU work issues
   // while those MFMAs occupy the matrix pipe
   auto step = [&](auto s_c) {
@@ -280,10 +287,10 @@ __device__ __forceinline__ void mfma_chunk(const T* buf, const int (&a_off)[MI],
     auto tile = [&](auto mi_c) {
       constexpr int mi = decltype(mi_c)::value;
 #pragma unroll
-      for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = Mma<T>::m32(af[mi], bq[s % D][ni], acc[mi][ni]);
-      if constexpr (s + 1 < STEPS) {
-        constexpr int tap = (s + 1) / KK, kk = (s + 1) % KK;
-        af[mi] = *reinterpret_cast<const u32x4*>(buf + a_off[mi] + (tap / KS) * ROW + (tap % KS) * PS + kk * 16);
+      for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = Mma<T>::m32(af[s % AD][mi], bq[s % D][ni], acc[mi][ni]);
+      if constexpr (s + AD < STEPS) {
+        constexpr int tap = (s + AD) / KK, kk = (s + AD) % KK;
+        af[s % AD][mi] = *reinterpret_cast<const u32x4*>(buf + a_off[mi] + (tap / KS) * ROW + (tap % KS) * PS + kk * 16);
       }
       if constexpr (SLICED) slice(std::integral_constant<int, s * MI + mi>{});
       if constexpr (VALU_PER_MFMA < 0) __builtin_amdgcn_sched_barrier(0);
@@ -631,10 +638,10 @@ void conv_mfma_kernel(MfmaParams p) {
       };
       // the last chunk activates a harmless reload into the buffer nobody reads: one instruction stream, no
       // control flow inside the pinned schedule
-      mfma_chunk<T, MI, NI, KT, KC, ROW, PS, D, true, SPREAD>(buf, a_off, wrsrc, bcur, bnext, tap_stride, kk_stride, lane16, bq, acc, slice);
+      mfma_chunk<T, MI, NI, KT, KC, ROW, PS, D, true, SPREAD, decltype(slice)&, (RING > 6 ? 2 : 1)>(buf, a_off, wrsrc, bcur, bnext, tap_stride, kk_stride, lane16, bq, acc, slice);
     } else {
       auto none = [](auto) {};
-      mfma_chunk<T, MI, NI, KT, KC, ROW, PS, D, false, -1>(buf, a_off, wrsrc, bcur, bnext, tap_stride, kk_stride, lane16, bq, acc, none);
+      mfma_chunk<T, MI, NI, KT, KC, ROW, PS, D, false, -1, decltype(none)&, (RING > 6 ? 2 : 1)>(buf, a_off, wrsrc, bcur, bnext, tap_stride, kk_stride, lane16, bq, acc, none);
       if (more) activate_all(c0n, nbuf);
     }
     issue(c + 2);
@@ -772,6 +779,9 @@ TileId pick_tile(const ConvArgs& a) {
     // per compute unit instead of three: it pays (6 to 8 %) where that still leaves every compute unit two workgroups
     // (the 240x360 layers of the decoder), and loses on smaller layers.
     if (a.cout % 256 == 0 && ((px + 127) / 128) * (a.cout / 256) >= 2 * 256) return T128x256;
+    // (a 96-pixel tile on 6x16 patches, which puts the 512 -> 512 layers at 60x90 on 240 instead of 192 compute units,
+    // measured 3 % on those layers: a lone workgroup's time is set by its weight stream, 1.2 MB through the vector
+    // L1 whatever its pixel count; not kept)
     return n128 ? T128x128_1x4 : T128x64;
   }
   if (n128 && a.cin % 64 == 0 && px * (a.cout / 128) >= 256L * 256 * 2) return T256x128;
