@@ -211,7 +211,7 @@ __device__ __forceinline__ void epilogue_store(const f32x16 (&acc)[MI][NI], floa
       if (n0 > 0.f) { const float ds = s0 / n0; m.n = n0; m.mean = a0 + ds; m.m2 = fmaxf(q0 - s0 * ds, 0.f); }
     }
     // channels of one group are cpg consecutive lanes
-    for (int mask = 1; mask < cpg; mask <<= 1) m = butterfly(m, lane, mask);
+    m = merge_to_first(m, lane, cpg);
     // (device-scope stores: another workgroup of this launch may merge them, see the row hand-over in the kernel)
     if (lane < CV * 8 && (lane & (cpg - 1)) == 0) store_device(stats + (size_t)((co_w + lane) / cpg) * stats_stride, m);
   }
@@ -579,7 +579,7 @@ void conv_mfma_kernel(MfmaParams p) {
 #pragma unroll
           for (int k = 0; k < 8; ++k) m = merge(m, t[k]);
         }
-        for (int mask = 1; mask < 8; mask <<= 1) m = butterfly(m, lane, mask);
+        m = merge_to_first(m, lane, 8);
         if (sub == 0) s_stat[g] = make_float2(m.mean, 1.0f / sqrtf(m.m2 / m.n + p.eps));
       }
       __syncthreads();
@@ -692,7 +692,7 @@ void conv_mfma_kernel(MfmaParams p) {
 #pragma unroll
           for (int k = 0; k < 8; ++k) m = merge(m, t[k]);
         }
-        for (int mask = 1; mask < 8; mask <<= 1) m = butterfly(m, lane, mask);
+        m = merge_to_first(m, lane, 8);
         if (sub == 0) p.rows_out[((size_t)n * p.stats_groups + g0 + gi) * p.tiles_y + tile_y] = m;
       }
     }

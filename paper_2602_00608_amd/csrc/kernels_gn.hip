@@ -199,7 +199,7 @@ __global__ __launch_bounds__(kFinThreads) void gn_finalize(const Moments* __rest
 #pragma unroll
     for (int k = 0; k < 4; ++k) m = merge(m, t[k]);
   }
-  for (int mask = 1; mask < 64; mask <<= 1) m = butterfly(m, lane, mask);   // lane-independent order
+  m = merge_to_first(m, lane, 64);   // fixed order
   if (lane == 0) s_w[tid >> 6] = m;
   __syncthreads();
   if (tid == 0) {

@@ -33,6 +33,27 @@ __device__ __forceinline__ Moments butterfly(Moments m, int lane, int mask) {
   return (lane & mask) ? merge(o, m) : merge(m, o);
 }
 
+// Lane i takes the triple of lane i + N of its row of 16 lanes (N = 1, 2, 4, 8), an empty triple if that lane lies
+// outside the row: a data-parallel-primitive move in the vector ALU, where the xor shuffle above is a trip through LDS.
+template <int N> __device__ __forceinline__ Moments row_down(Moments m) {
+  Moments r;
+  r.n = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, m.n), 0x100 + N, 0xf, 0xf, true));
+  r.mean = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, m.mean), 0x100 + N, 0xf, 0xf, true));
+  r.m2 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, m.m2), 0x100 + N, 0xf, 0xf, true));
+  return r;
+}
+// Merge of the `width` consecutive lanes (a power of two up to 64) that start at a lane whose index is a multiple of
+// `width`, left in that first lane, in a fixed order; the other lanes end with partial merges.
+__device__ __forceinline__ Moments merge_to_first(Moments m, int lane, int width) {
+  if (width > 1) m = merge(m, row_down<1>(m));
+  if (width > 2) m = merge(m, row_down<2>(m));
+  if (width > 4) m = merge(m, row_down<4>(m));
+  if (width > 8) m = merge(m, row_down<8>(m));
+  if (width > 16) m = butterfly(m, lane, 16);
+  if (width > 32) m = butterfly(m, lane, 32);
+  return m;
+}
+
 // Device-scope (write-through / L2-bypassing) accesses of a triple and the wait that orders a wavefront's stores before
 // a ticket it takes afterwards: the hand-over between workgroups of one launch that both the single-launch statistics
 // kernel and the convolution epilogue use (gfx950; see the note at the top of kernels_gn.hip).
