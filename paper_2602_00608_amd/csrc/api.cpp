@@ -35,6 +35,13 @@ int launch_conv(const ConvArgs& a, hipStream_t s) {
   return launch_conv_direct(a, s);
 }
 
+// Triples per (sample, group) that the kernel launch_conv picks for this shape emits with stats_ws set; 0: it emits none.
+static int conv_stats_slots(const ConvArgs& a) {
+  if (conv_taps_supported(a)) return 0;
+  if (conv_mfma_supported(a)) return conv_mfma_stats_slots(a);
+  return conv_small_cin_supported(a) ? conv_small_cin_stats_slots(a) : 0;
+}
+
 const char* conv_kernel_label(const ConvArgs& a) {
   if (conv_taps_supported(a)) return conv_taps_label(a);
   if (!conv_mfma_supported(a)) return conv_small_cin_supported(a) ? "conv_small_cin_kernel" : "conv_direct_kernel";
@@ -250,7 +257,7 @@ static void fuse_stats_into_producers(wmdec_decoder& d) {
     if (j < 0) continue;
     bool clash = false;
     for (size_t k = j + 1; k < i; ++k) clash |= d.steps[k].kind == Step::CONV && d.steps[k].emit_stats;
-    if (clash || conv_mfma_stats_slots(step_shape_args(d, d.steps[j], 1)) <= 0) continue;
+    if (clash || conv_stats_slots(step_shape_args(d, d.steps[j], 1)) <= 0) continue;
     d.steps[j].emit_stats = 1;
     st.from_producer = 1;
     st.bytes = 0.0;          // no tensor traffic left in this step
@@ -263,7 +270,7 @@ static void fuse_stats_into_producers(wmdec_decoder& d) {
     if (cons.kind != Step::CONV || !cons.norm || cons.src != st.src || !conv_mfma_supported(step_shape_args(d, cons, 1))) continue;
     if (conv_taps_supported(step_shape_args(d, cons, 1))) continue;   // that kernel takes mean / rstd only
     // A producer with few spatial tiles needs no merge of its own at all: the consumer reads its triples as they are.
-    const int slots = conv_mfma_stats_slots(step_shape_args(d, d.steps[j], 1));
+    const int slots = conv_stats_slots(step_shape_args(d, d.steps[j], 1));
     if (slots <= 128) {
       d.steps[j].emit_rows = parity;
       d.steps[j].emit_direct = 1;
@@ -274,6 +281,7 @@ static void fuse_stats_into_producers(wmdec_decoder& d) {
       d.launches -= 1;
       continue;
     }
+    if (!conv_mfma_supported(step_shape_args(d, d.steps[j], 1))) continue;   // only that kernel merges by row
     int rows = 0, ctiles = 0, per_row = 0;
     conv_mfma_row_extents(step_shape_args(d, d.steps[j], 1), &rows, &ctiles, &per_row);
     if (rows > 64) continue;   // keeps the consumer's merge short
@@ -401,7 +409,7 @@ static WsLayout ws_layout(const wmdec_decoder* d, int batch) {
   for (const Step& st : d->steps) {
     if (st.kind != Step::CONV || st.emit_rows < 0) continue;
     int rows = 0, ctiles = 0, per_row = 0;
-    if (st.emit_direct) { rows = conv_mfma_stats_slots(step_shape_args(*d, st, 1)); ctiles = 0; }
+    if (st.emit_direct) { rows = conv_stats_slots(step_shape_args(*d, st, 1)); ctiles = 0; }
     else conv_mfma_row_extents(step_shape_args(*d, st, 1), &rows, &ctiles, &per_row);
     if ((size_t)rows * ctiles > max_tickets) max_tickets = (size_t)rows * ctiles;
     if ((size_t)rows > max_rows) max_rows = rows;
@@ -419,7 +427,7 @@ static WsLayout ws_layout(const wmdec_decoder* d, int batch) {
   L.stats_ws_bytes = gn_stats_moments_bytes(batch, d->cfg.groups);
   for (const Step& st : d->steps) {
     if (st.kind != Step::CONV || !st.emit_stats) continue;
-    const size_t need = (size_t)batch * d->cfg.groups * conv_mfma_stats_slots(step_shape_args(*d, st, batch)) * 3 * sizeof(float);
+    const size_t need = (size_t)batch * d->cfg.groups * conv_stats_slots(step_shape_args(*d, st, batch)) * 3 * sizeof(float);
     if (need > L.stats_ws_bytes) L.stats_ws_bytes = need;
   }
   L.stats_ws = o; o += align_up(L.stats_ws_bytes, 256);
@@ -890,7 +898,7 @@ static int launch_step(wmdec_decoder* dec, const WsLayout& L, const Step& st, co
         a.n = batch; a.h = st.h; a.w = st.w; a.cin = st.cin; a.cout = st.cout; a.ksize = st.ksize; a.upsample = st.upsample;
         if (st.emit_stats) {
           a.stats_groups = c.groups;
-          (*emitted_slots) = conv_mfma_stats_slots(a);
+          (*emitted_slots) = conv_stats_slots(a);
           if ((*emitted_slots) > 0) a.stats_ws = st.emit_direct ? ws + L.rows[st.emit_rows] : ws + L.stats_ws;
           if (st.emit_rows >= 0 && !st.emit_direct) { a.rows_out = ws + L.rows[st.emit_rows]; a.tickets = ws + L.conv_tickets; }
         }
@@ -978,7 +986,7 @@ int decoder_time_step(wmdec_decoder* dec, const void* latent, const void* packed
   int emitted_slots = 0;   // what the emitting convolutions before this step left behind
   for (int i = 0; i < step; ++i) {
     const Step& st = dec->steps[i];
-    if (st.kind == Step::CONV && st.emit_stats) emitted_slots = conv_mfma_stats_slots(step_shape_args(*dec, st, batch));
+    if (st.kind == Step::CONV && st.emit_stats) emitted_slots = conv_stats_slots(step_shape_args(*dec, st, batch));
   }
   hipEvent_t e0, e1;
   WMDEC_HIP(hipEventCreate(&e0));

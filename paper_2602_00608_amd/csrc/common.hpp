@@ -109,6 +109,7 @@ struct ConvArgs {
 int launch_conv_direct(const ConvArgs& a, hipStream_t s);
 // same file: 3x3 convolution with at most 8 input channels, no normalisation / residual, NHWC output (conv_in)
 bool conv_small_cin_supported(const ConvArgs& a);
+int conv_small_cin_stats_slots(const ConvArgs& a);   // triples per (sample, group) it would emit with stats_ws set; 0: none
 int launch_conv_small_cin(const ConvArgs& a, hipStream_t s);
 // kernels_conv_mfma.hip: implicit-GEMM MFMA convolution; returns 1 if the shape
 // is not one it handles (caller falls back to the direct kernel), 0 if launched.

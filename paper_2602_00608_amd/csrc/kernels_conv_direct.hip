@@ -5,7 +5,7 @@
 // matrix-core kernel does not take (C_in = 4 of conv_in, C_out = 3 of conv_out).
 // For 16-bit operand types the activated input is rounded to that type before
 // the product and accumulated in fp32, i.e. the arithmetic of the MFMA kernel.
-#include "common.hpp"
+#include "moments.hpp"
 #include "pack_layout.hpp"
 
 namespace wmdec {
@@ -162,18 +162,22 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(DirectParams p) {
 // With x_step the input of sample n is formed while it is staged: x[0] + (n + 1) * step_scale * x_step (one fp32
 // fused multiply-add, then the one rounding to the operand type): n + 1 first-order extrapolation steps of a latent
 // along its motion vector (Alg. 2, hit branch), so a batch of extrapolated latents never exists in memory.
-constexpr int SP = 32;   // pixels per workgroup
+constexpr int SP = 48;    // pixels per workgroup: two segments per row of the 90-pixel latent
+constexpr int SCO = 64;   // output channels per workgroup: lane = channel
+constexpr int SQ = 4;     // the pixels of a segment are dealt to the four wavefronts in runs of SP / SQ
 
 template <int CI, typename TW_, typename TO>
 __global__ __launch_bounds__(256) void conv_small_cin_kernel(const void* __restrict__ x, int x_dtype, int x_nchw,
                                                              const void* __restrict__ x_step, float step_scale,
                                                              const TW_* __restrict__ w, const float* __restrict__ bias,
-                                                             TO* __restrict__ y, int h, int w_out, int cin, int cout) {
+                                                             TO* __restrict__ y, int h, int w_out, int cin, int cout,
+                                                             Moments* __restrict__ stats, int stats_cpg, int stats_groups) {
   __shared__ __align__(16) float s_in[3][SP + 2][CI];
-  const int tid = threadIdx.x;
+  __shared__ Moments s_m[SQ][SCO];
+  const int tid = threadIdx.x, lane = tid & 63, q = tid >> 6;
   const int segs = (w_out + SP - 1) / SP;
   const int oy = blockIdx.x / segs, x0 = (blockIdx.x % segs) * SP;
-  const int co = blockIdx.y * 256 + tid;
+  const int co = blockIdx.y * SCO + lane;
   const int n = blockIdx.z;
   for (int i = tid; i < 3 * (SP + 2) * CI; i += 256) {
     const int c = i % CI, hx = (i / CI) % (SP + 2), hy = i / (CI * (SP + 2));
@@ -199,27 +203,48 @@ __global__ __launch_bounds__(256) void conv_small_cin_kernel(const void* __restr
   }
   const float bv = bias ? bias[cc] : 0.f;
   __syncthreads();
-  if (co >= cout) return;
-  TO* yrow = y + (((size_t)n * h + oy) * w_out + x0) * cout + co;
+  const bool live = co < cout;
+  TO* yrow = y + (((size_t)n * h + oy) * w_out + x0) * cout + cc;
   const int npx = min(SP, w_out - x0);
-  for (int px = 0; px < npx; ++px) {
+  Moments m = {0.f, 0.f, 0.f};   // of this channel's stored values, one value at a time (Welford)
+  const int p0 = q * (SP / SQ), p1 = min(p0 + SP / SQ, npx);
+  for (int px = p0; px < p1; ++px) {
     float acc = bv;
 #pragma unroll
     for (int tap = 0; tap < 9; ++tap)
 #pragma unroll
       for (int c = 0; c < CI; ++c) acc = fmaf(s_in[tap / 3][px + tap % 3][c], wr[tap][c], acc);
-    yrow[(size_t)px * cout] = from_float<TO>(acc);
+    const TO stored = from_float<TO>(acc);
+    if (live) yrow[(size_t)px * cout] = stored;
+    const float v = to_float(stored), d = v - m.mean;
+    m.n += 1.f;
+    m.mean += d * __builtin_amdgcn_rcpf(m.n);
+    m.m2 = fmaf(d, v - m.mean, m.m2);
+  }
+  // GroupNorm moments of y for the next layer: the channels of a group are stats_cpg consecutive lanes (the launcher
+  // checks that groups do not straddle wavefronts or the end of the channels); the four wavefronts' triples of a group
+  // are merged in wavefront order: one triple per (sample, group, workgroup)
+  if (stats) {
+    s_m[q][lane] = merge_to_first(m, lane, stats_cpg);
+    __syncthreads();
+    if (q == 0 && live && lane % stats_cpg == 0) {
+      Moments t = s_m[0][lane];
+#pragma unroll
+      for (int k = 1; k < SQ; ++k) t = merge(t, s_m[k][lane]);
+      stats[((size_t)n * stats_groups + co / stats_cpg) * ((size_t)segs * h) + blockIdx.x] = t;
+    }
   }
 }
 
 template <int CI, typename TW_>
 int launch_small_cin_t(const ConvArgs& a, hipStream_t s) {
   const int segs = (a.w + SP - 1) / SP;
-  dim3 grid((unsigned)(segs * a.h), (unsigned)((a.cout + 255) / 256), (unsigned)a.n);
+  dim3 grid((unsigned)(segs * a.h), (unsigned)((a.cout + SCO - 1) / SCO), (unsigned)a.n);
+  const int cpg = a.stats_ws ? a.cout / a.stats_groups : 1;
   switch (a.y_dtype) {
-    case WMDEC_F32: hipLaunchKernelGGL((conv_small_cin_kernel<CI, TW_, float>), grid, dim3(256), 0, s, a.x, a.x_dtype, a.x_nchw, a.x_step, a.step_scale, (const TW_*)a.wt, a.bias, (float*)a.y, a.h, a.w, a.cin, a.cout); break;
-    case WMDEC_BF16: hipLaunchKernelGGL((conv_small_cin_kernel<CI, TW_, bf16_t>), grid, dim3(256), 0, s, a.x, a.x_dtype, a.x_nchw, a.x_step, a.step_scale, (const TW_*)a.wt, a.bias, (bf16_t*)a.y, a.h, a.w, a.cin, a.cout); break;
-    default: hipLaunchKernelGGL((conv_small_cin_kernel<CI, TW_, f16_t>), grid, dim3(256), 0, s, a.x, a.x_dtype, a.x_nchw, a.x_step, a.step_scale, (const TW_*)a.wt, a.bias, (f16_t*)a.y, a.h, a.w, a.cin, a.cout); break;
+    case WMDEC_F32: hipLaunchKernelGGL((conv_small_cin_kernel<CI, TW_, float>), grid, dim3(256), 0, s, a.x, a.x_dtype, a.x_nchw, a.x_step, a.step_scale, (const TW_*)a.wt, a.bias, (float*)a.y, a.h, a.w, a.cin, a.cout, (Moments*)a.stats_ws, cpg, a.stats_groups); break;
+    case WMDEC_BF16: hipLaunchKernelGGL((conv_small_cin_kernel<CI, TW_, bf16_t>), grid, dim3(256), 0, s, a.x, a.x_dtype, a.x_nchw, a.x_step, a.step_scale, (const TW_*)a.wt, a.bias, (bf16_t*)a.y, a.h, a.w, a.cin, a.cout, (Moments*)a.stats_ws, cpg, a.stats_groups); break;
+    default: hipLaunchKernelGGL((conv_small_cin_kernel<CI, TW_, f16_t>), grid, dim3(256), 0, s, a.x, a.x_dtype, a.x_nchw, a.x_step, a.step_scale, (const TW_*)a.wt, a.bias, (f16_t*)a.y, a.h, a.w, a.cin, a.cout, (Moments*)a.stats_ws, cpg, a.stats_groups); break;
   }
   WMDEC_HIP(hipGetLastError());
   return WMDEC_OK;
@@ -227,9 +252,18 @@ int launch_small_cin_t(const ConvArgs& a, hipStream_t s) {
 
 }  // namespace
 
+// Triples per (sample, group) this kernel emits for its output, 0 if it cannot: a group must be a power-of-two run of
+// at most 64 lanes (= channels), so that no group straddles a wavefront, a workgroup or the end of the channels.
+int conv_small_cin_stats_slots(const ConvArgs& a) {
+  if (a.stats_groups < 1 || a.cout % a.stats_groups != 0) return 0;
+  const int cpg = a.cout / a.stats_groups;
+  if (cpg > 64 || (cpg & (cpg - 1)) != 0) return 0;
+  return (a.w + SP - 1) / SP * a.h;
+}
+
 bool conv_small_cin_supported(const ConvArgs& a) {
-  return a.ksize == 3 && !a.upsample && a.cin <= 8 && !a.mean && !a.groups_norm && !a.res && !a.y_nchw && is_16bit(a.op_dtype) &&
-         a.stats_ws == nullptr;
+  return a.ksize == 3 && !a.upsample && a.cin <= 8 && !a.mean && !a.groups_norm && !a.rows_in && !a.res && !a.x2 && !a.y_nchw &&
+         is_16bit(a.op_dtype) && !a.rows_out && (a.stats_ws == nullptr || conv_small_cin_stats_slots(a) > 0);
 }
 
 int launch_conv_small_cin(const ConvArgs& a, hipStream_t s) {

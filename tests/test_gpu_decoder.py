@@ -438,7 +438,7 @@ def test_statistics_from_the_epilogue_match_the_statistics_pass():
 def test_statistics_hand_over_without_a_merge_launch():
     """Default graph: the last workgroup of every tile row of the producing convolution merges that row's partial
     moments, the consuming convolution merges the rows while it builds its scale/shift table.  Against the graph with
-    the merge launch: 29 launches fewer on the full decoder, both within the bar of the oracle, and the hand-over
+    the merge launch: 30 launches fewer on the full decoder, both within the bar of the oracle, and the hand-over
     (device-scope stores, a ticket per tile row) gives the same bits on every repetition."""
     chans = (512, 128, 64, 64)
     spec = synth.decoder_weight_spec(level_channels=chans, resblocks_per_level=2)
