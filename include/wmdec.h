@@ -128,9 +128,11 @@ int wmdec_gn_silu_conv3x3(const void* x, int act_dtype, const float* mean, const
  * workgroup writes per-group partial moments of its tile to `workspace`
  * (wmdec_conv_stats_workspace_bytes(...) bytes, no initialisation needed); a
  * second small launch merges them in a fixed order.
- * Only shapes the matrix-core kernel takes can emit moments: 16-bit act_dtype,
- * cin % 32 == 0, cout % 64 == 0, cout/out_groups a power of two <= 32;
- * otherwise WMDEC_ERR_UNSUPPORTED (the workspace query then returns 0). */
+ * Two kernels can emit moments, both for 16-bit act_dtype: the matrix-core
+ * kernel (cin % 32 == 0, cout % 64 == 0, cout/out_groups a power of two <= 32)
+ * and the kernel for cin <= 8 (the decoder's conv_in: no normalisation of x,
+ * no residual, cout/out_groups a power of two <= 64); any other shape gives
+ * WMDEC_ERR_UNSUPPORTED (the workspace query then returns 0). */
 size_t wmdec_conv_stats_workspace_bytes(int act_dtype, int y_dtype, int n, int h, int w, int cin,
                                         int cout, int out_groups);
 int wmdec_gn_silu_conv3x3_stats(const void* x, int act_dtype, const float* mean, const float* rstd,

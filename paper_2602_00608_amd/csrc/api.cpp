@@ -580,7 +580,7 @@ static ConvArgs stats_conv_shape(int act_dtype, int y_dtype, int n, int h, int w
 
 size_t wmdec_conv_stats_workspace_bytes(int act_dtype, int y_dtype, int n, int h, int w, int cin, int cout, int out_groups) {
   if (n <= 0 || h <= 0 || w <= 0 || cin <= 0 || cout <= 0 || out_groups <= 0 || !valid_dtype(act_dtype) || !valid_dtype(y_dtype)) return 0;
-  const int slots = conv_mfma_stats_slots(stats_conv_shape(act_dtype, y_dtype, n, h, w, cin, cout, out_groups));
+  const int slots = conv_stats_slots(stats_conv_shape(act_dtype, y_dtype, n, h, w, cin, cout, out_groups));
   return (size_t)n * out_groups * slots * 3 * sizeof(float);
 }
 
@@ -599,10 +599,11 @@ int wmdec_gn_silu_conv3x3_stats(const void* x, int act_dtype, const float* mean,
   a.x = x; a.mean = mean; a.rstd = mean ? rstd : nullptr; a.gamma = gamma; a.beta = beta;
   a.groups = mean ? groups : 1; a.silu = (mean && apply_silu) ? 1 : 0;
   a.wt = w_packed; a.bias = bias; a.res = residual; a.y = y;
-  const int slots = conv_mfma_stats_slots(a);
+  const int slots = conv_stats_slots(a);
   WMDEC_REQUIRE(slots > 0, WMDEC_ERR_UNSUPPORTED,
-                "%s: this shape / type does not take the matrix-core kernel that emits moments (16-bit types, cin %% 32 == 0, "
-                "cout %% 64 == 0, channels per output group a power of two <= 32); use wmdec_gn_stats on y", who);
+                "%s: this shape / type takes no kernel that emits moments (16-bit types and either cin %% 32 == 0, cout %% 64 == 0, "
+                "channels per output group a power of two <= 32, or cin <= 8 without normalisation and residual, channels per "
+                "output group a power of two <= 64); use wmdec_gn_stats on y", who);
   const size_t need = (size_t)n * out_groups * slots * 3 * sizeof(float);
   WMDEC_REQUIRE(workspace && aligned16(workspace) && workspace_bytes >= need, WMDEC_ERR_WORKSPACE,
                 "%s: workspace needs %zu bytes, got %zu", who, need, workspace_bytes);

@@ -213,6 +213,9 @@ def test_gn_silu_conv3x3(dtype, ydtype, n, cin, cout, h, w, norm, silu, bias, re
     ("f16", "f16", 1, 256, 256, 240, 360, True),    # 128 x 128 tile with one weight fragment per four MFMAs
     ("f16", "f16", 1, 128, 128, 480, 720, True),    # 256 x 128 tile (full-resolution layer)
     ("bf16", "bf16", 1, 128, 128, 480, 720, False),
+    ("f16", "f16", 1, 4, 512, 60, 90, False),       # conv_in: the kernel for few input channels, no normalisation of x
+    ("bf16", "bf16", 2, 4, 64, 13, 37, False),      # two channels per group, ragged segment, two samples
+    ("f16", "f16", 1, 8, 2048, 5, 50, False),       # 64 channels per group: a group is a whole wavefront
 ])
 def test_conv_epilogue_statistics(dtype, ydtype, n, cin, cout, h, w, residual):
     """wmdec_gn_silu_conv3x3_stats: mean / rstd of the tensor the kernel stored, per (sample, output group), must
@@ -224,16 +227,17 @@ def test_conv_epilogue_statistics(dtype, ydtype, n, cin, cout, h, w, residual):
     b = (b + 0.5).astype(np.float32)                 # a mean well away from zero
     xd = G.dev_nhwc(x, dtype)
     res = G.dev_nhwc(G.stored(r.standard_normal((n, cout, h, w)), dtype), dtype) if residual else None
-    mean, rstd = G.gn_stats(xd, groups, eps)
-    gamma = G.dev_f32((1 + 0.2 * r.standard_normal(cin)).astype(np.float32))
-    beta = G.dev_f32((0.2 * r.standard_normal(cin)).astype(np.float32))
+    norm = cin % groups == 0
+    mean, rstd = G.gn_stats(xd, groups, eps) if norm else (None, None)
+    gamma = G.dev_f32((1 + 0.2 * r.standard_normal(cin)).astype(np.float32)) if norm else None
+    beta = G.dev_f32((0.2 * r.standard_normal(cin)).astype(np.float32)) if norm else None
     y = torch.empty((n, h, w, cout), dtype=G.TORCH[ydtype], device="cuda")
     nbytes = wmdec.conv_stats_workspace_bytes(G.ENUM[dtype], G.ENUM[ydtype], n, h, w, cin, cout, groups)
     assert nbytes > 0
     ws = torch.full((nbytes,), 0xA5, dtype=torch.uint8, device="cuda")     # needs no initialisation
     mo = torch.empty(n * groups, dtype=torch.float32, device="cuda")
     ro = torch.empty(n * groups, dtype=torch.float32, device="cuda")
-    wmdec.gn_silu_conv3x3_stats(xd, mean, rstd, gamma, beta, groups, True, G.pack(wt, dtype), G.dev_f32(b), res, y,
+    wmdec.gn_silu_conv3x3_stats(xd, mean, rstd, gamma, beta, groups, norm, G.pack(wt, dtype), G.dev_f32(b), res, y,
                                 groups, eps, mo, ro, ws)
     torch.cuda.synchronize()
     wm, wr = ref.gn_stats(G.host_nchw(y), groups, eps)
@@ -244,7 +248,7 @@ def test_conv_epilogue_statistics(dtype, ydtype, n, cin, cout, h, w, residual):
     assert float(torch.max(torch.abs(mo - m2) * r2)) < 2e-5 and float(torch.max(torch.abs(ro / r2 - 1.0))) < 2e-5
     # the tensor itself is the one the plain entry point writes
     y2 = torch.empty_like(y)
-    wmdec.gn_silu_conv3x3(xd, mean, rstd, gamma, beta, groups, True, G.pack(wt, dtype), G.dev_f32(b), res, y2)
+    wmdec.gn_silu_conv3x3(xd, mean, rstd, gamma, beta, groups, norm, G.pack(wt, dtype), G.dev_f32(b), res, y2)
     assert torch.equal(y, y2)
 
 
