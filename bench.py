@@ -52,7 +52,8 @@ def main():
     ap.add_argument("--separate-shortcut", action="store_true",
                     help="ablation: the 1x1 shortcuts are launches of their own instead of contraction steps of conv2")
     ap.add_argument("--calibration-copy", action="store_true",
-                    help="first copy 256 MiB device to device three times: a kernel of known traffic for counter passes")
+                    help="first copy 256 MiB device to device three times with the library's plain copy kernel: "
+                         "launches of known traffic for counter passes")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (frames shard over GPUs with no exchange; "
@@ -71,7 +72,7 @@ def main():
         src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
         for _ in range(3):
-            dst.copy_(src)
+            wmdec.measure_copy(src, dst)
         torch.cuda.synchronize()
         del src, dst
 

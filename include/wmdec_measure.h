@@ -43,6 +43,14 @@ int decoder_step_times(const wmdec_decoder* dec, float* ms, int count);
 int decoder_time_step(wmdec_decoder* dec, const void* latent, const void* packed, void* out, int batch,
                       int step, int reps, float* ms_per_launch, void* stream);
 
+/* A plain copy of `bytes` bytes (a multiple of 16; both device pointers 16-byte
+ * aligned, not overlapping) by one kernel, copy_u128_kernel, in which every
+ * thread loads and stores 16 bytes: it reads and writes exactly `bytes` bytes
+ * of HBM, which is what passes of hardware traffic counters over the benchmark
+ * are scaled by (the counters' units differ between machines).  For callers
+ * that measure; nothing in a decoder run uses it.  Asynchronous on `stream`. */
+int wmdec_measure_copy(const void* src, void* dst, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

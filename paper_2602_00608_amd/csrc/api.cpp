@@ -628,6 +628,15 @@ int wmdec_upsample2x_conv3x3(const void* x, int act_dtype, const void* w_packed,
                     nullptr, y, y_dtype, n, 2 * h_in, 2 * w_in, cin, cout, stream);
 }
 
+int wmdec_measure_copy(const void* src, void* dst, size_t bytes, void* stream) {
+  WMDEC_REQUIRE(src && dst, WMDEC_ERR_INVALID_ARG, "measure_copy: null pointer");
+  WMDEC_REQUIRE(aligned16(src) && aligned16(dst) && bytes % 16 == 0, WMDEC_ERR_INVALID_ARG,
+                "measure_copy: pointers and byte count must be multiples of 16");
+  const char* a = (const char*)src; const char* b = (const char*)dst;
+  WMDEC_REQUIRE(a + bytes <= b || b + bytes <= a, WMDEC_ERR_INVALID_ARG, "measure_copy: src and dst must not overlap");
+  return launch_copy_u128(src, dst, bytes, (hipStream_t)stream);
+}
+
 int wmdec_upsample2x_nearest(const void* x, void* y, int dtype, int n, int h_in, int w_in, int c, void* stream) {
   WMDEC_REQUIRE(x && y, WMDEC_ERR_INVALID_ARG, "upsample2x_nearest: null pointer");
   WMDEC_REQUIRE(valid_dtype(dtype), WMDEC_ERR_INVALID_ARG, "upsample2x_nearest: bad dtype");

@@ -158,6 +158,7 @@ int launch_pack_upconv(const void* src, int src_dtype, int cout, int cin, void* 
 int launch_transpose(const void* src, int src_dtype, void* dst, int dst_dtype, int batch, int rows, int cols,
                      size_t src_ld, size_t src_batch_stride, size_t dst_ld, size_t dst_batch_stride, hipStream_t s);
 int launch_copy_f32(const float* src, float* dst, size_t count, hipStream_t s);
+int launch_copy_u128(const void* src, void* dst, size_t bytes, hipStream_t s);   // bytes % 16 == 0
 // out[i] = fma(scale, v[i], z[i]) in fp32, rounded once to out_dtype; z, v of `dtype`
 int launch_axpy(const void* z, const void* v, int dtype, float scale, void* out, int out_dtype, size_t count, hipStream_t s);
 int launch_zero_u32(void* p, int count, hipStream_t s);   // a fill kernel (safe under graph capture, unlike a memset node)

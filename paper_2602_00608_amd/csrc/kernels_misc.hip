@@ -117,6 +117,12 @@ __global__ __launch_bounds__(256) void copy_f32_kernel(const float* __restrict__
   if (i < count) dst[i] = src[i];
 }
 
+// plain copy, 16 bytes per thread: a kernel of known traffic that hardware counter passes are scaled by
+__global__ __launch_bounds__(256) void copy_u128_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t count) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < count) dst[i] = src[i];
+}
+
 // one first-order extrapolation step count folded into `scale`: out = z + scale * v (Alg. 2, hit branch)
 template <typename S, typename D>
 __global__ __launch_bounds__(256) void axpy_kernel(const S* __restrict__ z, const S* __restrict__ v, float scale,
@@ -257,6 +263,15 @@ __global__ void zero_u32_kernel(unsigned* p, int count) {
 
 int launch_zero_u32(void* p, int count, hipStream_t s) {
   hipLaunchKernelGGL(zero_u32_kernel, dim3((unsigned)((count + 63) / 64)), dim3(64), 0, s, (unsigned*)p, count);
+  WMDEC_HIP(hipGetLastError());
+  return WMDEC_OK;
+}
+
+int launch_copy_u128(const void* src, void* dst, size_t bytes, hipStream_t s) {
+  const size_t count = bytes / 16;
+  if (count == 0) return WMDEC_OK;
+  WMDEC_REQUIRE((count + 255) / 256 <= 0x7fffffffu, WMDEC_ERR_UNSUPPORTED, "copy: too many bytes for one launch");
+  hipLaunchKernelGGL(copy_u128_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, (const uint4*)src, (uint4*)dst, count);
   WMDEC_HIP(hipGetLastError());
   return WMDEC_OK;
 }

@@ -18,7 +18,7 @@ import re
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-CALIBRATION_KERNEL = "__amd_rocclr_copyBuffer"
+CALIBRATION_KERNEL = "copy_u128_kernel"
 CALIBRATION_KIB = 256 * 1024          # one calibration copy reads and writes 256 MiB
 
 

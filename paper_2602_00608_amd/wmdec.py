@@ -85,6 +85,7 @@ SIGNATURES = {
                                ctypes.POINTER(ctypes.c_double)]),
     "decoder_step_times": (_i, [_vp, ctypes.POINTER(ctypes.c_float), _i]),
     "decoder_time_step": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, ctypes.POINTER(ctypes.c_float), _vp]),
+    "wmdec_measure_copy": (_i, [_vp, _vp, ctypes.c_size_t, _vp]),
 }
 
 _lib = None
@@ -191,6 +192,11 @@ def gn_silu_conv3x3_stats(x, mean, rstd, gamma, beta, groups, apply_silu, w_pack
         _ptr(w_packed), _ptr(bias), _ptr(residual), _ptr(y), dtype_enum(y), n, h, w, x.shape[3], y.shape[3],
         out_groups, out_eps, _ptr(mean_out), _ptr(rstd_out), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream()))
+
+
+def measure_copy(src, dst):
+    """Plain copy of src into dst (same byte count, a multiple of 16) by one kernel of known traffic."""
+    _check(lib().wmdec_measure_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), _stream()))
 
 
 def gn_conv1x1(x, mean, rstd, gamma, beta, groups, apply_silu, w_packed, bias, residual, y):

@@ -483,3 +483,23 @@ def test_adaln_fused_projection_limits():
     with pytest.raises(wmdec.WmdecError) as e:
         wmdec.adaln_fused_projection(c, w, None, out)
     assert e.value.status == wmdec.ERR_UNSUPPORTED
+
+
+# ------------------------------------------------------------------ measurement helper: the plain copy of known traffic
+@pytest.mark.parametrize("nbytes", [16, 16 * 255, (1 << 20) + 16 * 7, 256 << 20])
+def test_measure_copy_bit_exact(nbytes):
+    """wmdec_measure_copy moves exactly the bytes it is given (counter passes are scaled by its traffic) and nothing
+    next to them; sizes and pointers that are not multiples of 16, and overlapping ranges, are refused."""
+    g = torch.Generator(device="cuda").manual_seed(nbytes % 9973)
+    src = torch.randint(0, 256, (nbytes,), dtype=torch.uint8, device="cuda", generator=g)
+    big = torch.full((nbytes + 512,), 0x5A, dtype=torch.uint8, device="cuda")
+    dst = big[256:256 + nbytes]
+    wmdec.measure_copy(src, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    assert bool((big[:256] == 0x5A).all()) and bool((big[256 + nbytes:] == 0x5A).all())
+    if nbytes >= 64:
+        for bad_src, bad_dst in ((src[:24], dst[:24]), (src[8:40], dst[:32]), (big[:64], big[32:96])):
+            with pytest.raises(wmdec.WmdecError) as e:
+                wmdec.measure_copy(bad_src, bad_dst)
+            assert e.value.status == wmdec.ERR_INVALID_ARG
