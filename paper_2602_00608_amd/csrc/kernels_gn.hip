@@ -179,8 +179,8 @@ __global__ __launch_bounds__(256) void gn_partial_any(const T* __restrict__ x, i
 }
 
 // grid = n*groups workgroups of 1024 threads: thread t merges slots t, t+1024, ... in order (loaded four at a
-// time: a row of up to 4096 slots costs one memory round trip), then a fixed butterfly over each wavefront, then
-// the 16 wavefronts in order.
+// time: a row of up to 4096 slots costs one memory round trip), then a fixed merge tree over each wavefront, then
+// over the 16 wavefronts.
 constexpr int kFinThreads = 1024;
 __global__ __launch_bounds__(kFinThreads) void gn_finalize(const Moments* __restrict__ ws, int chunks, float eps,
                                                            float* __restrict__ mean, float* __restrict__ rstd) {
@@ -202,12 +202,14 @@ __global__ __launch_bounds__(kFinThreads) void gn_finalize(const Moments* __rest
   m = merge_to_first(m, lane, 64);   // fixed order
   if (lane == 0) s_w[tid >> 6] = m;
   __syncthreads();
-  if (tid == 0) {
-    m = s_w[0];
-#pragma unroll
-    for (int k = 1; k < kFinThreads / 64; ++k) m = merge(m, s_w[k]);
-    mean[ng] = m.mean;
-    rstd[ng] = 1.0f / sqrtf(m.m2 / m.n + eps);
+  if (tid < 64) {   // the 16 wavefront results: four merge levels inside one row of lanes instead of a chain of 15
+    static_assert(kFinThreads / 64 == 16, "one row of 16 lanes");
+    m = tid < kFinThreads / 64 ? s_w[tid] : Moments{0.f, 0.f, 0.f};
+    m = merge_to_first(m, lane, 16);
+    if (tid == 0) {
+      mean[ng] = m.mean;
+      rstd[ng] = 1.0f / sqrtf(m.m2 / m.n + eps);
+    }
   }
 }
 
