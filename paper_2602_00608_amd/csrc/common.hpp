@@ -23,11 +23,8 @@ __device__ __forceinline__ float to_float(f16_t v) {
 template <typename T> __device__ __forceinline__ T from_float(float v);
 template <> __device__ __forceinline__ float from_float<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16_t from_float<bf16_t>(float v) {
-  // round to nearest even; NaN stays NaN
-  uint32_t u = __float_as_uint(v);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return bf16_t{(uint16_t)((u >> 16) | 0x40u)};
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return bf16_t{(uint16_t)(u >> 16)};
+  __bf16 h = (__bf16)v;  // v_cvt_pk_bf16_f32: round to nearest even; NaN stays NaN
+  bf16_t r; __builtin_memcpy(&r.bits, &h, 2); return r;
 }
 template <> __device__ __forceinline__ f16_t from_float<f16_t>(float v) {
   _Float16 h = (_Float16)v;  // v_cvt_f16_f32: round to nearest even

@@ -48,6 +48,14 @@ template <> __device__ __forceinline__ uint32_t pack2<f16_t>(float a, float b) {
   v.y = (_Float16)b;
   return __builtin_bit_cast(uint32_t, v);
 }
+// bf16 likewise: one v_cvt_pk_bf16_f32 for the pair
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+template <> __device__ __forceinline__ uint32_t pack2<bf16_t>(float a, float b) {
+  bf16x2_t v;
+  v.x = (__bf16)a;
+  v.y = (__bf16)b;
+  return __builtin_bit_cast(uint32_t, v);
+}
 template <typename T> __device__ __forceinline__ float unpack_lo(uint32_t w) { return to_float(T{(uint16_t)(w & 0xffffu)}); }
 template <typename T> __device__ __forceinline__ float unpack_hi(uint32_t w) { return to_float(T{(uint16_t)(w >> 16)}); }
 
