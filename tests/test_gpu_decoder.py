@@ -298,7 +298,7 @@ def test_time_step_repeats_a_step_without_changing_the_frame():
 def test_decoder_run_replays_from_a_captured_graph():
     """decoder_run enqueues only kernels (no memset nodes, no allocation, no synchronisation), so a caller can
     capture it in a HIP graph: every replay, with eager runs and synchronisations in between, must reproduce
-    the eager frame bit for bit."""
+    the eager frame bit for bit.  Likewise decoder_run_extrapolated, the batched decode of extrapolated latents."""
     cfg = small_cfg(wmdec.F16)
     spec = synth.decoder_weight_spec(level_channels=(512, 128, 64, 32), resblocks_per_level=2)
     weights = synth.draw_params(spec, synth.weight_seed(9), random_affine=True)
@@ -330,6 +330,24 @@ def test_decoder_run_replays_from_a_captured_graph():
         torch.cuda.synchronize()
         assert torch.equal(out, eager)
     del graph
+    # the batched decode of extrapolated latents (Alg. 2, hit branch), captured the same way
+    vd = (0.25 * zd.float()).to(torch.bfloat16)
+    dec.run_extrapolated(zd[:1], vd[:1], 0.75, packed, out)
+    torch.cuda.synchronize()
+    eager_x = out.clone()
+    assert not torch.equal(eager_x, eager)
+    graph_x = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph_x):
+        dec.run_extrapolated(zd[:1], vd[:1], 0.75, packed, out)
+    for _ in range(3):
+        out.zero_()
+        graph_x.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager_x)
+        dec.run(zd, packed, out)        # another graph's worth of eager work on the same workspace in between
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager)
+    del graph_x
     dec.close()
 
 
